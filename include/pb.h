@@ -1,0 +1,142 @@
+/*
+ * pb.h -- C ABI of the MI355X (gfx950) PrecisionBatching hot path.
+ *
+ * The library computes the bit-decomposed quantized matrix product of
+ * "Quantized Neural Network Inference with Precision Batching"
+ * (arXiv 2003.00822): a B-bit weight matrix is stored as B packed 1-bit
+ * bitlayers (Section 3.2, Algorithm 1), fp32 activations are converted to
+ * 32-bit fixed point and split into bit planes that are batched as extra
+ * columns (Section 3.1, Algorithm 2), products are AND + population count on
+ * packed words (Section 3.4), and the per-bitlayer results are scaled and
+ * accumulated over the first `bits_used` bitlayers, a number chosen per call
+ * (abstract; Section 1).
+ *
+ * Conventions
+ *  - Every pointer is a DEVICE pointer unless its comment says "host".
+ *  - Matrices are dense row-major.  Device pointers must be 16-byte aligned.
+ *  - The caller owns every buffer, including `packed` and `workspace`; the
+ *    library allocates and frees nothing, keeps no state and never
+ *    synchronises.  All work is enqueued on `stream` (a hipStream_t passed as
+ *    void*, NULL = the default stream); calls on different streams may run
+ *    concurrently as long as they use different workspaces and outputs.
+ *  - Every function returns PB_OK (0) or a negative pb_status; nothing
+ *    throws or aborts.  Argument errors are detected on the host before
+ *    anything is launched.  A HIP launch failure returns PB_EHIP
+ *    (pb_last_hip_error() gives the HIP code); a fault inside a kernel
+ *    surfaces at the caller's next synchronisation, as for any HIP work.
+ *  - Weights and activations are assumed finite; a NaN activation converts
+ *    to 0 and +-inf saturates (see pb_matmul).
+ */
+#ifndef PB_H
+#define PB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum pb_status {
+    PB_OK = 0,
+    PB_EINVAL = -1, /* null pointer, non-positive size, bits / bits_used / batch out of range */
+    PB_EALIGN = -2, /* a device pointer is not 16-byte aligned */
+    PB_ESIZE = -3,  /* shape beyond what the kernels support (see PB_MAX_*) */
+    PB_EHIP = -4    /* a HIP call failed */
+} pb_status;
+
+#define PB_MAX_BITS 16       /* stored bitlayers B, 1..16 (Section 1: "1-16 bit execution") */
+#define PB_MAX_COLS 32768    /* columns of one weight matrix */
+#define PB_MAX_BATCH 4096    /* activation vectors per call */
+#define PB_LAYOUT_ROWMAJOR_V1 0x50420001u
+
+/* Shape and format of one packed weight matrix (host struct, plain data).
+ * bits      B, the number of stored bitlayers = two's-complement width of the
+ *           weight codes, sign layer included (the paper's "PBatch-n" stores
+ *           n+1 layers: bits = n+1; Table 1 caption).
+ * frac_bits f, position of the activations' fixed point (Section 3.1: 16, "may
+ *           be changed").
+ * act_bits  k, number of activation bit planes (Algorithm 2: 32).
+ * layout    tag of the packed layout (PB_LAYOUT_*), filled by pb_desc_init. */
+typedef struct pb_desc {
+    int32_t rows, cols, bits;
+    int32_t frac_bits;
+    int32_t act_bits;
+    uint32_t layout;
+} pb_desc;
+
+/* Fill *d (host) for a rows x cols matrix with `bits` bitlayers and the
+ * defaults f = 16, k = 32.  PB_EINVAL / PB_ESIZE on bad shapes. */
+int pb_desc_init(pb_desc *d, int rows, int cols, int bits);
+
+/* Bytes the caller must allocate for `packed` (all B bitlayers, padded),
+ * and for `workspace` of a call with `batch` activation vectors (bit planes,
+ * plane statistics, and for pb_lstm_cell the gate pre-activations).
+ * Return 0 if the descriptor is invalid. */
+size_t pb_packed_bytes(const pb_desc *d);
+size_t pb_workspace_bytes(const pb_desc *d, int batch);
+
+/* Algorithm 1 (preprocessing, offline): quantize W to B-bit codes on a
+ * symmetric linear grid, q = round_half_even(W / step), step = max|W| /
+ * (2^(B-1) - 1) (Section 3.3; step = max|W| for B = 1, step = 1 for W = 0),
+ * split the two's-complement codes into B bitlayers, sign layer first
+ * (Section 3.2), pack 32 columns per word (Section 3.4) and write the layer
+ * scales scales[i] = step * s_i, s_0 = -2^(B-1), s_i = 2^(B-1-i).
+ *   W       [rows][cols] fp32, read only
+ *   packed  pb_packed_bytes() bytes, written (opaque layout, see pb_unpack)
+ *   scales  [bits] fp32, written
+ * Launches a few kernels on `stream`; nothing is returned to the host. */
+int pb_quantize_pack(const float *W, int rows, int cols, int bits, void *packed, float *scales, void *stream);
+
+/* Inverse of the packing, for checking: q[r][c] = the B-bit code stored for
+ * element (r, c), sign-extended to int32.  q: [rows][cols], written. */
+int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);
+
+/* Algorithm 2 (inference).  For each of the `batch` activation vectors:
+ *   x_q = trunc(x * 2^f) as a k-bit two's-complement integer (saturating;
+ *   NaN -> 0), split into k bit planes with weights 2^j and -2^(k-1);
+ *   A_i[r] = sum_j c_j * popcount(row r of bitlayer i AND plane j)  (exact, int64)
+ *   Y[r]   = fp32( sum_{i < bits_used} scales[i] * A_i[r] * 2^-f )  (sum in fp64)
+ * Only the first `bits_used` bitlayers (sign layer and the next bits_used-1)
+ * are read: the accuracy / speed knob of the abstract.
+ *   packed, scales  as written by pb_quantize_pack (scales may be any fp32 values)
+ *   d               host descriptor
+ *   X               [batch][cols] fp32, read only
+ *   Y               [batch][rows] fp32, written
+ *   workspace       pb_workspace_bytes(d, batch) bytes, overwritten
+ * The activation conversion and bit transposition are part of the call. */
+int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X, int batch,
+              float *Y, void *workspace, void *stream);
+
+/* Same product, but returns the exact integer accumulators instead of Y:
+ * A[i][n][r] = sum_c bit_i[r][c] * x_q[n][c], int64, for i < bits_used.
+ * A: [bits_used][batch][rows], written. */
+int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
+                  void *workspace, void *stream);
+
+/* The fixed-point activations alone (Algorithm 2, x_q = Int(x * 2^f)), for
+ * checking: xq [batch][cols] int32, written; workspace as for pb_matmul
+ * (the bit planes are left in it). */
+int pb_fixed_point(const pb_desc *d, const float *X, int batch, int32_t *xq, void *workspace, void *stream);
+
+/* One LSTM cell step on top of pb_matmul (Sections 4.2-4.3: the LSTM's input
+ * and hidden linear maps run through the quantized product, nonlinearities in
+ * fp32).  The packed matrix is the fused gate matrix, rows = 4H in gate order
+ * (input, forget, cell, output), cols = I + H, applied to [x_t ; h_prev]:
+ *   g = W [x_t ; h_prev] + bias,  c' = sigmoid(g_f) c + sigmoid(g_i) tanh(g_g),
+ *   h' = sigmoid(g_o) tanh(c').
+ *   x_t [batch][I], h_prev, c_prev [batch][H], bias [4H] or NULL: read only
+ *   h_out, c_out [batch][H]: written (may alias h_prev / c_prev)
+ *   input_size = I; H = d->rows / 4; d->cols must equal I + H. */
+int pb_lstm_cell(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *x_t,
+                 int input_size, const float *h_prev, const float *c_prev, const float *bias, float *h_out,
+                 float *c_out, int batch, void *workspace, void *stream);
+
+/* Text for a pb_status; the HIP error code of the last PB_EHIP on this thread. */
+const char *pb_strerror(int status);
+int pb_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PB_H */

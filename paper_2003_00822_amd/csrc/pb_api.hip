@@ -1,0 +1,185 @@
+// Host side of the C ABI declared in include/pb.h: argument checks, workspace
+// carving and kernel dispatch.  No device memory is allocated or freed here and
+// nothing synchronises; every kernel goes to the caller's stream.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pb.h"
+#include "pb_kernels.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int check_desc(const pb_desc *d, pb::Layout *L)
+{
+    if (!d) return PB_EINVAL;
+    if (d->rows < 1 || d->cols < 1 || d->bits < 1 || d->bits > PB_MAX_BITS) return PB_EINVAL;
+    if (d->frac_bits < 0 || d->frac_bits > 30) return PB_EINVAL;
+    if (d->act_bits < 2 || d->act_bits > 32) return PB_EINVAL;
+    if (d->layout != PB_LAYOUT_ROWMAJOR_V1) return PB_EINVAL;
+    if (d->cols > PB_MAX_COLS) return PB_ESIZE;
+    if (!pb::make_layout(d->rows, d->cols, d->bits, L)) return PB_ESIZE;
+    if (pb::packed_bytes(*L) > 0xFFFFFFFFull) return PB_ESIZE;  // tiles are addressed with 32-bit byte offsets
+    return PB_OK;
+}
+
+int hip_status(int err)
+{
+    if (err == 0) return PB_OK;
+    g_last_hip_error = err;
+    return PB_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pb_desc_init(pb_desc *d, int rows, int cols, int bits)
+{
+    if (!d) return PB_EINVAL;
+    if (rows < 1 || cols < 1 || bits < 1 || bits > PB_MAX_BITS) return PB_EINVAL;
+    if (cols > PB_MAX_COLS) return PB_ESIZE;
+    d->rows = rows;
+    d->cols = cols;
+    d->bits = bits;
+    d->frac_bits = 16;
+    d->act_bits = 32;
+    d->layout = PB_LAYOUT_ROWMAJOR_V1;
+    pb::Layout L;
+    return check_desc(d, &L);
+}
+
+size_t pb_packed_bytes(const pb_desc *d)
+{
+    pb::Layout L;
+    if (check_desc(d, &L) != PB_OK) return 0;
+    return pb::packed_bytes(L);
+}
+
+size_t pb_workspace_bytes(const pb_desc *d, int batch)
+{
+    pb::Layout L;
+    if (check_desc(d, &L) != PB_OK || batch < 1 || batch > PB_MAX_BATCH) return 0;
+    return pb::workspace_bytes(L, batch);
+}
+
+int pb_quantize_pack(const float *W, int rows, int cols, int bits, void *packed, float *scales, void *stream)
+{
+    pb_desc d;
+    int rc = pb_desc_init(&d, rows, cols, bits);
+    if (rc != PB_OK) return rc;
+    if (!W || !packed || !scales) return PB_EINVAL;
+    if (!aligned16(W) || !aligned16(packed) || !aligned16(scales)) return PB_EALIGN;
+    pb::Layout L;
+    pb::make_layout(rows, cols, bits, &L);
+    return hip_status(pb::launch_quantize_pack(W, L, static_cast<uint32_t *>(packed), scales,
+                                               static_cast<hipStream_t>(stream)));
+}
+
+int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!packed || !q) return PB_EINVAL;
+    if (!aligned16(packed) || !aligned16(q)) return PB_EALIGN;
+    return hip_status(pb::launch_unpack(static_cast<const uint32_t *>(packed), L, q, static_cast<hipStream_t>(stream)));
+}
+
+static int matmul_common(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X0,
+                         int cols0, const float *X1, int cols1, int batch, float *Y, int64_t *A, void *workspace,
+                         void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!packed || !X0 || !workspace || (!Y && !A) || (Y && !scales)) return PB_EINVAL;
+    if (bits_used < 1 || bits_used > d->bits) return PB_EINVAL;
+    if (batch < 1) return PB_EINVAL;
+    if (batch > PB_MAX_BATCH) return PB_ESIZE;
+    if (!aligned16(packed) || !aligned16(X0) || !aligned16(workspace) || (Y && !aligned16(Y)) ||
+        (A && !aligned16(A)) || (scales && !aligned16(scales)) || (X1 && !aligned16(X1)))
+        return PB_EALIGN;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    int *meta = reinterpret_cast<int *>(ws + pb::ws_meta_off(L, batch));
+    uint32_t *planes = reinterpret_cast<uint32_t *>(ws + pb::ws_planes_off(L, batch));
+    int err = pb::launch_prep(X0, cols0, X1, cols1, batch, L, d->frac_bits, d->act_bits, planes, meta, nullptr, st);
+    if (err) return hip_status(err);
+    err = pb::launch_matvec(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits, planes, meta,
+                            batch, Y, reinterpret_cast<long long *>(A), st);
+    return hip_status(err);
+}
+
+int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X, int batch,
+              float *Y, void *workspace, void *stream)
+{
+    if (!Y || !d) return PB_EINVAL;
+    return matmul_common(packed, scales, d, bits_used, X, d->cols, nullptr, 0, batch, Y, nullptr, workspace, stream);
+}
+
+int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
+                  void *workspace, void *stream)
+{
+    if (!A || !d) return PB_EINVAL;
+    return matmul_common(packed, nullptr, d, bits_used, X, d->cols, nullptr, 0, batch, nullptr, A, workspace, stream);
+}
+
+int pb_fixed_point(const pb_desc *d, const float *X, int batch, int32_t *xq, void *workspace, void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!X || !xq || !workspace) return PB_EINVAL;
+    if (batch < 1) return PB_EINVAL;
+    if (batch > PB_MAX_BATCH) return PB_ESIZE;
+    if (!aligned16(X) || !aligned16(xq) || !aligned16(workspace)) return PB_EALIGN;
+    char *ws = static_cast<char *>(workspace);
+    int *meta = reinterpret_cast<int *>(ws + pb::ws_meta_off(L, batch));
+    uint32_t *planes = reinterpret_cast<uint32_t *>(ws + pb::ws_planes_off(L, batch));
+    return hip_status(pb::launch_prep(X, d->cols, nullptr, 0, batch, L, d->frac_bits, d->act_bits, planes, meta, xq,
+                                      static_cast<hipStream_t>(stream)));
+}
+
+int pb_lstm_cell(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *x_t,
+                 int input_size, const float *h_prev, const float *c_prev, const float *bias, float *h_out,
+                 float *c_out, int batch, void *workspace, void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!x_t || !h_prev || !c_prev || !h_out || !c_out || !workspace) return PB_EINVAL;
+    if (d->rows % 4 != 0 || input_size < 1 || input_size >= d->cols) return PB_EINVAL;
+    const int H = d->rows / 4;
+    if (d->cols != input_size + H) return PB_EINVAL;
+    if (batch < 1) return PB_EINVAL;
+    if (batch > PB_MAX_BATCH) return PB_ESIZE;
+    if (!aligned16(h_prev) || !aligned16(c_prev) || !aligned16(h_out) || !aligned16(c_out) ||
+        (bias && !aligned16(bias)))
+        return PB_EALIGN;
+    float *gates = reinterpret_cast<float *>(static_cast<char *>(workspace) + pb::ws_gates_off(L, batch));
+    rc = matmul_common(packed, scales, d, bits_used, x_t, input_size, h_prev, H, batch, gates, nullptr, workspace,
+                       stream);
+    if (rc != PB_OK) return rc;
+    return hip_status(pb::launch_lstm_pointwise(gates, bias, c_prev, H, batch, h_out, c_out,
+                                                static_cast<hipStream_t>(stream)));
+}
+
+const char *pb_strerror(int status)
+{
+    switch (status) {
+        case PB_OK: return "ok";
+        case PB_EINVAL: return "invalid argument (null pointer, non-positive size, bits/bits_used/batch out of range)";
+        case PB_EALIGN: return "device pointer not 16-byte aligned";
+        case PB_ESIZE: return "shape beyond the supported maximum";
+        case PB_EHIP: return "HIP call failed (see pb_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+int pb_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

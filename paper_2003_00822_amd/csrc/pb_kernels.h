@@ -1,0 +1,29 @@
+// Internal: launchers implemented by the .hip files of this library.
+// Each returns a hipError_t value as int (0 = success); arguments are validated by the caller.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "pb_layout.h"
+
+namespace pb {
+
+// pb_quantize.hip
+int launch_quantize_pack(const float *W, const Layout &L, uint32_t *packed, float *scales, hipStream_t st);
+int launch_unpack(const uint32_t *packed, const Layout &L, int32_t *q, hipStream_t st);
+
+// pb_prep.hip: fp32 activations -> fixed point -> bit planes + plane statistics.
+// Row n of the activations is the concatenation [X0[n][0..cols0) ; X1[n][0..cols1)] (X1 may be null with cols1 = 0).
+int launch_prep(const float *X0, int cols0, const float *X1, int cols1, int batch, const Layout &L, int frac_bits,
+                int act_bits, uint32_t *planes, int *meta, int32_t *xq_out, hipStream_t st);
+
+// pb_matvec.hip: AND + popcount product against register-resident planes, one launch for all bitlayers.
+// Exactly one of Y / A is non-null.
+int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
+                  const uint32_t *planes, const int *meta, int batch, float *Y, long long *A, hipStream_t st);
+
+// pb_lstm.hip: gate nonlinearities and state update on the gate pre-activations.
+int launch_lstm_pointwise(const float *gates, const float *bias, const float *c_prev, int H, int batch, float *h_out,
+                          float *c_out, hipStream_t st);
+
+}  // namespace pb

@@ -1,0 +1,231 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded
+inputs.  Integer accumulators and codes bit-exact; fp32 outputs within 1e-5 relative."""
+import numpy as np
+import pytest
+
+torch = pytest.importorskip("torch")
+
+from oracle import pb_oracle as po
+from paper_2003_00822_amd import synth
+from tests.helpers import assert_y_close, oracle_reference
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def pb():
+    assert torch.cuda.is_available(), "gpu tests need a GPU"
+    from paper_2003_00822_amd import pb as pbmod
+    pbmod.lib()  # fails loudly if the HIP library is missing
+    return pbmod
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def run_layer(pb, W, bits, X, m_list, frac_bits=16, act_bits=32, check_y=True):
+    R, C = W.shape
+    N = X.shape[0]
+    lin = pb.PackedLinear(dev(W), bits, max_batch=N, frac_bits=frac_bits, act_bits=act_bits)
+    prep = po.prepare(W, bits)
+    # Algorithm 1: codes and scales
+    q_gpu = lin.unpack().cpu().numpy()
+    assert (q_gpu == prep["q"]).all(), "quantized codes differ"
+    sc_gpu = lin.scales[:bits].cpu().numpy()
+    assert (sc_gpu.view(np.int32) == prep["scales"].view(np.int32)).all(), "scales differ"
+    Xd = dev(X)
+    for m in m_list:
+        ref = oracle_reference(W, bits, X, m, frac_bits=frac_bits, act_bits=act_bits)
+        A_gpu = lin.acc(Xd, m).cpu().numpy()
+        assert A_gpu.shape == ref["A"].shape
+        bad = A_gpu != ref["A"]
+        assert not bad.any(), "int64 accumulators differ at %s (R=%d C=%d bits=%d m=%d)" % (
+            np.argwhere(bad)[:5].tolist(), R, C, bits, m)
+        if check_y:
+            Y_gpu = lin(Xd, m).cpu().numpy()
+            assert_y_close(Y_gpu, ref["Y"], ref["A"], prep["scales"], frac_bits=frac_bits)
+    return lin
+
+
+SHAPES = [
+    (1, 1), (3, 5), (4, 32), (5, 33), (7, 64), (16, 127), (33, 128), (10, 4096), (64, 96), (130, 784),
+    (257, 1024), (100, 3000), (33, 4100), (17, 8192 + 5), (9, 16384), (4100, 40), (6, 12000),
+]
+
+
+@pytest.mark.parametrize("shape", SHAPES)
+def test_shapes_all_layers(pb, shape):
+    R, C = shape
+    bits = 1 + (R + C) % 8
+    W, X = synth.ragged(R, C, batch=1, case=1)
+    print("shape", shape, "bits", bits, flush=True)
+    run_layer(pb, W, bits, X, sorted({1, bits, max(1, bits // 2)}))
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6, 7, 8, 12, 16])
+def test_every_bit_width_and_prefix(pb, bits):
+    W, X = synth.ragged(70, 200, batch=1, case=bits, xdist="uniform")
+    print("bits", bits, flush=True)
+    run_layer(pb, W, bits, X, list(range(1, bits + 1)))
+
+
+@pytest.mark.parametrize("xdist", ["normal", "uniform", "relu", "wide"])
+def test_activation_distributions(pb, xdist):
+    W, X = synth.ragged(96, 1000, batch=3, case=3, xdist=xdist)
+    print("xdist", xdist, flush=True)
+    run_layer(pb, W, 4, X, [1, 4])
+
+
+def test_fixed_point_conversion(pb):
+    u = 2.0 ** -16
+    special = [0.0, 1.0, -2.0, 0.5 * u, -0.5 * u, 1.5 * u, -1.5 * u, 1.0 - 2.0 ** -24, 32767.998046875, 32768.0,
+               -32768.0, -32768.5, 1e30, -1e30, float("inf"), float("-inf"), float("nan"), -0.0]
+    rng = np.random.default_rng(4)
+    x = np.concatenate([np.array(special, dtype=np.float32),
+                        (rng.normal(size=3000) * np.exp2(rng.integers(-30, 18, size=3000))).astype(np.float32)])
+    X = x.reshape(1, -1)
+    for (f, k) in [(16, 32), (8, 32), (16, 16), (4, 8), (0, 4)]:
+        d = pb.pb_desc_init(4, X.shape[1], 2, frac_bits=f, act_bits=k)
+        ws = pb.alloc_workspace(d, 1)
+        xq = torch.empty(X.shape, dtype=torch.int32, device="cuda")
+        pb.pb_fixed_point(d, dev(X), 1, xq, ws)
+        want = po.fixed_point(X, frac_bits=f, act_bits=k)
+        assert (xq.cpu().numpy() == want).all(), (f, k)
+
+
+def test_special_activation_vectors(pb):
+    R, C, bits = 37, 200, 5
+    W, _ = synth.ragged(R, C, case=2)
+    cases = {
+        "zeros": np.zeros((1, C), dtype=np.float32),
+        "minus_one_lsb": np.full((1, C), -1.0 / 65536, dtype=np.float32),   # x_q = -1: every plane all ones
+        "int32_min": np.full((1, C), -40000.0, dtype=np.float32),           # only the negative top plane
+        "int32_max": np.full((1, C), 40000.0, dtype=np.float32),
+        "tiny": np.full((1, C), 1.0 / 65536, dtype=np.float32),             # x_q = 1: one plane
+    }
+    onehot = np.zeros((1, C), dtype=np.float32)
+    onehot[0, 131] = -3.25
+    cases["onehot"] = onehot
+    for name, X in cases.items():
+        print("special", name, flush=True)
+        run_layer(pb, W, bits, X, [1, 3, 5])
+
+
+def test_reduced_activation_precision(pb):
+    # Section 3.1: k (activation precision) of 8 or 16 planes; the fixed point moves with it
+    W, X = synth.ragged(50, 300, batch=2, case=5, xdist="uniform")
+    for (f, k) in [(6, 8), (14, 16), (20, 32)]:
+        print("act", f, k, flush=True)
+        run_layer(pb, W, 4, X, [2, 4], frac_bits=f, act_bits=k)
+
+
+def test_config1_fc_1024_definition_level(pb):
+    """Config 1, checked against the byte-per-bit tier of the oracle (Algorithm 2 taken literally)."""
+    W, X = synth.fc_small()
+    bits = 4
+    prep = po.prepare(W, bits)
+    lin = pb.PackedLinear(dev(W), bits)
+    for m in range(1, bits + 1):
+        A, T, Y = po.matmul_bitserial(prep["layers"], prep["scales"], prep["s"], m, X)
+        A_gpu = lin.acc(dev(X), m).cpu().numpy()
+        assert (A_gpu == A).all()
+        Y_gpu = lin(dev(X), m).cpu().numpy()
+        assert_y_close(Y_gpu, Y, A, prep["scales"])
+
+
+@pytest.mark.parametrize("bits", [8, 3])
+def test_config2_fc_4096_full_size(pb, bits):
+    W, X = synth.fc_square(4096, 0.02)
+    print("cfg2 bits", bits, flush=True)
+    run_layer(pb, W, bits, X, list(range(1, bits + 1)))
+
+
+def test_config3_mlp_layers(pb):
+    """Config 3: each layer fed with the oracle's previous-layer output (ReLU), so integers must match."""
+    Ws, X = synth.mlp()
+    bits = 6
+    x = X
+    for li, W in enumerate(Ws):
+        print("mlp layer", li, W.shape, flush=True)
+        m = [bits, 2, 4][li]
+        run_layer(pb, W, bits, x, [m])
+        ref = oracle_reference(W, bits, x, m)
+        x = np.maximum(ref["Y"], 0.0).astype(np.float32)
+
+
+def test_config5_large_fc_batch(pb):
+    W, X = synth.fc_large(batch=4)
+    print("cfg5 8192 batch 4", flush=True)
+    run_layer(pb, W, 2, X, [2])
+    W16, X16 = synth.ragged(64, 8192, batch=16, case=9)
+    run_layer(pb, W16, 8, X16, [8])
+
+
+def test_extra_16384(pb):
+    W, X = synth.fc_square(16384, 0.01, cfg=6)
+    bits = 2
+    lin = pb.PackedLinear(dev(W), bits)
+    # oracle on sampled rows only (full size in the launch configuration of the benchmark)
+    rng = np.random.default_rng(0)
+    rows = sorted(rng.choice(16384, size=48, replace=False).tolist() + [0, 16383])
+    A_gpu = lin.acc(dev(X), bits).cpu().numpy()
+    Y_gpu = lin(dev(X), bits).cpu().numpy()
+    prep = po.prepare(W, bits)
+    xq = po.fixed_point(X)
+    for r in rows:
+        sub = po.layer_products_direct(prep["layers"][:, r:r + 1, :], bits, xq)
+        assert (A_gpu[:, :, r] == sub[:, :, 0]).all(), r
+        y = po.dequant(sub[:, 0, :], prep["scales"], bits)
+        assert_y_close(Y_gpu[:, r], y, sub[:, 0, :], prep["scales"])
+
+
+def test_lstm_cell_config4(pb):
+    """Config 4: 35 sequential LSTM steps.  Integer parity is checked per step with oracle-fed state
+    (teacher forcing); the free-running GPU recurrence is compared to a tolerance."""
+    H = I = 1500
+    W, xs, bias = synth.lstm(H, I, steps=35)
+    bits, m = 4, 4
+    prep = po.prepare(W, bits)
+    lw = po.pack_words(prep["layers"])
+    lin = pb.PackedLinear(dev(W), bits)
+    d, packed, scales, ws = lin.desc, lin.packed, lin.scales, lin.workspace
+    bias_d = dev(bias)
+    h_or = np.zeros((1, H), dtype=np.float32)
+    c_or = np.zeros((1, H), dtype=np.float32)
+    h_free = torch.zeros((1, H), device="cuda")
+    c_free = torch.zeros((1, H), device="cuda")
+    for t in range(35):
+        xin = np.concatenate([xs[t], h_or], axis=1)
+        A_or, Y_or = po.matmul_words(lw, prep["scales"], m, I + H, xin)
+        if t in (0, 1, 17, 34):
+            A_gpu = lin.acc(dev(xin), m).cpu().numpy()
+            assert (A_gpu == A_or).all(), "step %d" % t
+        # one GPU step from the oracle's state
+        h_in, c_in = dev(h_or), dev(c_or)
+        h_out = torch.empty_like(h_in)
+        c_out = torch.empty_like(c_in)
+        pb.pb_lstm_cell(packed, scales, d, m, dev(xs[t]), I, h_in, c_in, bias_d, h_out, c_out, 1, ws)
+        h_new, c_new = po.lstm_pointwise(Y_or, bias, c_or)
+        assert np.abs(h_out.cpu().numpy() - h_new).max() < 2e-6, "step %d" % t
+        assert np.abs(c_out.cpu().numpy() - c_new).max() < 2e-6, "step %d" % t
+        # free-running GPU recurrence (in place)
+        pb.pb_lstm_cell(packed, scales, d, m, dev(xs[t]), I, h_free, c_free, bias_d, h_free, c_free, 1, ws)
+        h_or, c_or = h_new, c_new
+    assert np.abs(h_free.cpu().numpy() - h_or).max() < 1e-4
+    assert np.abs(c_free.cpu().numpy() - c_or).max() < 1e-4
+
+
+def test_errors_surface_as_status(pb):
+    d = pb.pb_desc_init(8, 64, 4)
+    X = torch.zeros((1, 64), device="cuda")
+    Y = torch.zeros((1, 8), device="cuda")
+    packed = pb.alloc_packed(d)
+    ws = pb.alloc_workspace(d, 1)
+    sc = torch.zeros(4, device="cuda")
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_matmul(packed, sc, d, 5, X, 1, Y, ws)
+    assert e.value.status == pb.PB_EINVAL
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_matmul(packed, sc, d, 4, X[:, 1:].contiguous()[:, :0].reshape(-1).new_zeros(65)[1:], 1, Y, ws)
+    assert e.value.status == pb.PB_EALIGN
