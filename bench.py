@@ -1,0 +1,255 @@
+#!/usr/bin/env python3
+"""Benchmark of the PrecisionBatching hot path on one MI355X.
+
+A step is one pass of the whole path (activation conversion + bit transpose, AND/popcount
+product, plane and bitlayer accumulation) over one batch-1 activation vector for every
+bits_used = 1..B of one FC layer (default: 4096 x 4096, B = 8): B calls of pb_matmul.
+Weights are resident in HBM before the timed region; each call reads a different copy out of
+a pool larger than the last-level cache, so the weight stream really comes from HBM ("cold").
+
+Prints ONE JSON line: effective weight GB/s (bytes of the bitlayers a call must read / time),
+matvecs/s, per-bits_used table, the roofline of the dominant kernel and the CPU oracle timed
+on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
+ALU_PEAK_GOPS = 256 * 4 * 16 * 2.4          # CUs x SIMDs x lanes x GHz = 39321.6 G int32 lane-ops/s
+LLC_BYTES = 256 << 20                       # last-level (Infinity) cache
+POOL_BYTES = 768 << 20                      # weight copies rotated through: 3x the last-level cache
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--size", type=int, default=4096, help="FC layer is size x size (4096 = the headline config)")
+    ap.add_argument("--bits", type=int, default=8, help="stored bitlayers B; bits_used sweeps 1..B")
+    ap.add_argument("--warm", action="store_true", help="reuse one weight copy (cache-resident) instead of the pool")
+    ap.add_argument("--eager", action="store_true", help="plain launches from Python instead of HIP graph replay")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--detail", default=None, help="also write the JSON (indented) to this file")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards by output rows across GPUs, see DESIGN.md); "
+              "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2003_00822_amd import pb, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    pb.lib()
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    n, B = args.size, args.bits
+    std = {4096: 0.02, 8192: 0.01}.get(n, 0.01)
+    W, X = synth.fc_square(n, std, batch=1, cfg=2 if n == 4096 else 5)
+    Wd = torch.from_numpy(W).to(dev)
+    Xd = torch.from_numpy(X).to(dev)
+    d = pb.pb_desc_init(n, n, B)
+    packed = pb.alloc_packed(d, dev)
+    scales = torch.empty(max(B, 4), dtype=torch.float32, device=dev)
+    pb.pb_quantize_pack(Wd, n, n, B, packed, scales)
+    torch.cuda.synchronize()
+    del Wd
+    pbytes = packed.numel()
+    copies = 1 if args.warm else max(2, -(-POOL_BYTES // pbytes))
+    pool = [packed] + [packed.clone() for _ in range(copies - 1)]
+    ws = pb.alloc_workspace(d, 1, dev)
+    Y = torch.empty((1, n), dtype=torch.float32, device=dev)
+    layer_bytes = pbytes // B   # bytes of one packed bitlayer (padding included)
+
+    # Work lists.  A "round" visits every weight copy once: G = copies // B steps of B calls (bits_used 1..B).
+    # Rounds are captured into HIP graphs so that the Python launch overhead (several microseconds per call,
+    # more than a kernel lasts) is outside the measurement; --eager times plain launches instead.
+    G = max(1, copies // B)
+
+    def round_calls():
+        i = 0
+        for _ in range(G):
+            for m in range(1, B + 1):
+                pb.pb_matmul(pool[i % copies], scales, d, m, Xd, 1, Y, ws)
+                i += 1
+
+    def capture(fn):
+        if args.eager:
+            return fn
+        fn()                                   # first call outside capture (lazy module load etc.)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return g.replay
+
+    def timed(fn, iters):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e-3 / iters   # seconds per iteration
+
+    # ---- the timed region of the contract: W warmup steps, K timed steps (rounded up to whole rounds) ----
+    run_round = capture(round_calls)
+    stream = torch.cuda.current_stream()
+    for _ in range(-(-args.warmup // G)):
+        run_round()
+    rounds = -(-args.steps // G)
+    steps = rounds * G
+    sec_per_step = timed(run_round, rounds) / G
+    step_bytes = layer_bytes * B * (B + 1) // 2
+    value = step_bytes / sec_per_step / 1e9
+
+    # plane statistics of this input (written by the activation kernel): planes actually multiplied
+    meta = ws[:64].view(torch.int32).cpu().numpy()
+    nplanes = int(meta[3])
+
+    # ---- per bits_used: whole call (prep + product) and the product kernel alone ----
+    per_m = []
+    kern_time_sum = 0.0
+    reps = max(2, -(-max(50, args.steps) // copies))
+
+    def call_loop(m):
+        def f():
+            for i in range(copies):
+                pb.pb_matmul(pool[i], scales, d, m, Xd, 1, Y, ws)
+        return f
+
+    def kern_loop(m):
+        def f():
+            for i in range(copies):
+                pb.pb_matmul_prepared(pool[i], scales, d, m, 1, Y, ws)
+        return f
+
+    pb.pb_act_prep(d, Xd, 1, ws)
+    for m in range(1, B + 1):
+        t_call = timed(capture(call_loop(m)), reps) / copies
+        t_kern = timed(capture(kern_loop(m)), reps) / copies
+        kern_time_sum += t_kern
+        wbytes = layer_bytes * m
+        lane_ops = 2.0 * nplanes * (wbytes / 4)      # one AND + one popcount-accumulate per (word, plane)
+        per_m.append({
+            "bits_used": m,
+            "us_per_call": round(t_call * 1e6, 3),
+            "matvecs_per_s": round(1.0 / t_call, 1),
+            "eff_weight_GBps": round(wbytes / t_call / 1e9, 1),
+            "kernel_us": round(t_kern * 1e6, 3),
+            "kernel_GBps": round(wbytes / t_kern / 1e9, 1),
+            "kernel_hbm_frac": round(wbytes / t_kern / 1e9 / HBM_PEAK_GBS, 4),
+            "kernel_alu_frac": round(lane_ops / t_kern / 1e9 / ALU_PEAK_GOPS, 4),
+        })
+
+    def prep_loop():
+        for _ in range(copies):
+            pb.pb_act_prep(d, Xd, 1, ws)
+    t_prep = timed(capture(prep_loop), reps) / copies
+
+    # ---- roofline of the dominant kernel (k_matvec) over the sweep bits_used = 1..B ----
+    avg_kernel_s = kern_time_sum / B
+    avg_bytes = step_bytes / B
+    avg_lane_ops = 2.0 * nplanes * (avg_bytes / 4)
+    hbm_frac = avg_bytes / avg_kernel_s / 1e9 / HBM_PEAK_GBS
+    alu_frac = avg_lane_ops / avg_kernel_s / 1e9 / ALU_PEAK_GOPS
+    roof_hbm = {"bound": "hbm", "achieved": round(avg_bytes / avg_kernel_s / 1e9, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(hbm_frac, 4), "traffic": None}
+    roof_alu = {"bound": "alu", "achieved": round(avg_lane_ops / avg_kernel_s / 1e9, 1),
+                "peak": round(ALU_PEAK_GOPS, 1), "unit": "Gop/s", "frac": round(alu_frac, 4), "traffic": None}
+    binding, other = (roof_alu, roof_hbm) if alu_frac > hbm_frac else (roof_hbm, roof_alu)
+    binding["kernel"] = other["kernel"] = "k_matvec"
+    binding["avg_launch_us"] = other["avg_launch_us"] = round(avg_kernel_s * 1e6, 3)
+    binding["active_planes"] = nplanes
+
+    out = {
+        "metric": "effective weight GB/s + matvecs/sec at bits_used=1..8 (batch 1); % HBM roofline",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(sec_per_step * 1e3, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32 popcount / int64 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "FC %dx%d, weight bitlayers B=%d, bits_used swept 1..%d (one call each per step), "
+                               "batch 1, x~N(0,1) as 32-bit fixed point" % (n, n, B, B),
+                   "weights": "cold: %d copies (%d MiB) rotated" % (copies, copies * pbytes >> 20) if not args.warm
+                   else "warm: one copy, cache resident",
+                   "launch": "eager" if args.eager else "hip graph replay (%d steps per graph)" % G,
+                   "active_planes": nplanes},
+        "matvecs_per_s": round(B / sec_per_step, 1),
+        "hbm_frac_whole_call": round(value / HBM_PEAK_GBS, 4),
+        "prep_kernel_us": round(t_prep * 1e6, 3),
+        "per_bits_used": per_m,
+        "roofline": binding,
+        "roofline_other": other,
+    }
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(W, X, B, layer_bytes)
+
+    line = json.dumps(out)
+    if args.detail:
+        with open(args.detail, "w") as f:
+            json.dump(out, f, indent=1)
+    print(line, flush=True)
+
+
+def cpu_baseline(W, X, B, layer_bytes):
+    """The oracle's packed-word tier (plain C, uint64 AND + popcount), timed as it stands on the host cores:
+    the same sweep bits_used = 1..B, rows split over threads, repeated for a bounded time."""
+    import numpy as np
+    from concurrent.futures import ThreadPoolExecutor
+
+    from oracle import pb_oracle as po
+
+    R, C = W.shape
+    prep = po.prepare(W, B)
+    lw = po.pack_words(prep["layers"])
+    threads = max(1, min(16, os.cpu_count() or 1))
+    bounds = [(R * t // threads, R * (t + 1) // threads) for t in range(threads)]
+
+    def sweep(pool):
+        for m in range(1, B + 1):
+            list(pool.map(lambda b: po.matmul_words(lw, prep["scales"], m, C, X, r0=b[0], r1=b[1], want_A=False),
+                          bounds))
+
+    with ThreadPoolExecutor(threads) as pool:
+        t0 = time.perf_counter()
+        sweep(pool)
+        one = time.perf_counter() - t0
+        reps = int(min(20, max(1, 10.0 / max(one, 1e-3))))
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            sweep(pool)
+        dt = (time.perf_counter() - t0) / reps
+    step_bytes = layer_bytes * B * (B + 1) // 2
+    return {"value": round(step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "sample": "oracle packed-word tier (uint64 AND+popcount, gcc -O2), full %dx%d layer, bits_used 1..%d, "
+                      "%d sweeps, %.2f s each" % (R, C, B, reps, dt),
+            "matvecs_per_s": round(B / dt, 2)}
+
+
+if __name__ == "__main__":
+    main()

@@ -114,6 +114,18 @@ int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bit
 int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
                   void *workspace, void *stream);
 
+/* The two halves of pb_matmul, for callers that apply several weight matrices
+ * to the same activations (or that time the halves separately):
+ * pb_act_prep converts X to fixed point and writes its bit planes and plane
+ * statistics into `workspace` (Algorithm 2, x_q = Int(x * 2^f), and the bitwise
+ * transpose of Section 3.4); pb_matmul_prepared runs the AND + popcount product
+ * and the scale-accumulation on planes left there by pb_act_prep for a
+ * descriptor with the same cols, frac_bits and act_bits and the same batch.
+ * pb_matmul(...) == pb_act_prep(...) followed by pb_matmul_prepared(...). */
+int pb_act_prep(const pb_desc *d, const float *X, int batch, void *workspace, void *stream);
+int pb_matmul_prepared(const void *packed, const float *scales, const pb_desc *d, int bits_used, int batch, float *Y,
+                       void *workspace, void *stream);
+
 /* The fixed-point activations alone (Algorithm 2, x_q = Int(x * 2^f)), for
  * checking: xq [batch][cols] int32, written; workspace as for pb_matmul
  * (the bit planes are left in it). */

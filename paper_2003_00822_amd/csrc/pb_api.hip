@@ -128,6 +128,40 @@ int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const flo
     return matmul_common(packed, nullptr, d, bits_used, X, d->cols, nullptr, 0, batch, nullptr, A, workspace, stream);
 }
 
+int pb_act_prep(const pb_desc *d, const float *X, int batch, void *workspace, void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!X || !workspace) return PB_EINVAL;
+    if (batch < 1) return PB_EINVAL;
+    if (batch > PB_MAX_BATCH) return PB_ESIZE;
+    if (!aligned16(X) || !aligned16(workspace)) return PB_EALIGN;
+    char *ws = static_cast<char *>(workspace);
+    int *meta = reinterpret_cast<int *>(ws + pb::ws_meta_off(L, batch));
+    uint32_t *planes = reinterpret_cast<uint32_t *>(ws + pb::ws_planes_off(L, batch));
+    return hip_status(pb::launch_prep(X, d->cols, nullptr, 0, batch, L, d->frac_bits, d->act_bits, planes, meta,
+                                      nullptr, static_cast<hipStream_t>(stream)));
+}
+
+int pb_matmul_prepared(const void *packed, const float *scales, const pb_desc *d, int bits_used, int batch, float *Y,
+                       void *workspace, void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!packed || !scales || !Y || !workspace) return PB_EINVAL;
+    if (bits_used < 1 || bits_used > d->bits) return PB_EINVAL;
+    if (batch < 1) return PB_EINVAL;
+    if (batch > PB_MAX_BATCH) return PB_ESIZE;
+    if (!aligned16(packed) || !aligned16(scales) || !aligned16(Y) || !aligned16(workspace)) return PB_EALIGN;
+    char *ws = static_cast<char *>(workspace);
+    const int *meta = reinterpret_cast<const int *>(ws + pb::ws_meta_off(L, batch));
+    const uint32_t *planes = reinterpret_cast<const uint32_t *>(ws + pb::ws_planes_off(L, batch));
+    return hip_status(pb::launch_matvec(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
+                                        planes, meta, batch, Y, nullptr, static_cast<hipStream_t>(stream)));
+}
+
 int pb_fixed_point(const pb_desc *d, const float *X, int batch, int32_t *xq, void *workspace, void *stream)
 {
     pb::Layout L;

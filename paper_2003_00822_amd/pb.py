@@ -21,7 +21,7 @@ PB_MAX_BATCH = 4096
 
 EXPORTS = [
     "pb_desc_init", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
-    "pb_matmul_acc", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
+    "pb_matmul_acc", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
 ]
 
 
@@ -65,6 +65,10 @@ def lib():
         L.pb_matmul.restype = _I
         L.pb_matmul_acc.argtypes = [_P, _D, _I, _P, _I, _P, _P, _P]
         L.pb_matmul_acc.restype = _I
+        L.pb_act_prep.argtypes = [_D, _P, _I, _P, _P]
+        L.pb_act_prep.restype = _I
+        L.pb_matmul_prepared.argtypes = [_P, _P, _D, _I, _I, _P, _P, _P]
+        L.pb_matmul_prepared.restype = _I
         L.pb_fixed_point.argtypes = [_D, _P, _I, _P, _P, _P]
         L.pb_fixed_point.restype = _I
         L.pb_lstm_cell.argtypes = [_P, _P, _D, _I, _P, _I, _P, _P, _P, _P, _P, _I, _P, _P]
@@ -151,6 +155,18 @@ def pb_matmul_acc(packed, d, bits_used, X, batch, A, workspace, stream=None):
     _check(lib().pb_matmul_acc(_ptr(packed, torch.uint8, "packed"), ctypes.byref(d), bits_used,
                                _ptr(X, torch.float32, "X"), batch, _ptr(A, torch.int64, "A"),
                                _ptr(workspace, torch.uint8, "workspace"), _stream(stream)), "pb_matmul_acc")
+
+
+def pb_act_prep(d, X, batch, workspace, stream=None):
+    _check(lib().pb_act_prep(ctypes.byref(d), _ptr(X, torch.float32, "X"), batch,
+                             _ptr(workspace, torch.uint8, "workspace"), _stream(stream)), "pb_act_prep")
+
+
+def pb_matmul_prepared(packed, scales, d, bits_used, batch, Y, workspace, stream=None):
+    _check(lib().pb_matmul_prepared(_ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float32, "scales"),
+                                    ctypes.byref(d), bits_used, batch, _ptr(Y, torch.float32, "Y"),
+                                    _ptr(workspace, torch.uint8, "workspace"), _stream(stream)),
+           "pb_matmul_prepared")
 
 
 def pb_fixed_point(d, X, batch, xq, workspace, stream=None):
