@@ -8,6 +8,7 @@
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "pb.h"
 
@@ -38,8 +39,10 @@ inline bool make_layout(int rows, int cols, int bits, Layout *L)
     L->cw = (cols + 31) / 32;
     int best_ws = 0, best_pad = 0;
     const int cand[3] = {128, 64, 32};
+    const char *force = getenv("PB_TUNE_WS");
     for (int k = 0; k < 3; ++k) {
         int ws = cand[k];
+        if (force && atoi(force) != ws) continue;
         int cs = (L->cw + ws - 1) / ws;
         if (cs > kMaxWavesPerWG) continue;
         int pad = cs * ws;

@@ -28,6 +28,7 @@
 // the schedule.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "pb_kernels.h"
 
@@ -104,69 +105,69 @@ __device__ __forceinline__ void tile_counts(const uint2 w, const uint32_t (&pr)[
     }
 }
 
-template <int NPASS>
-__device__ __forceinline__ void matvec_body(const MatvecArgs &a, char *smem)
+// Per-wave constants shared by the prologue and the body.
+struct WaveCtx {
+    int lane, wave, slice, rw, n;
+    int gbase, gcount, T;          // this wave's row groups and tile count (gcount * m)
+    int voff;                      // this lane's byte offset inside a tile
+    uint32_t soff;                 // byte offset of the next tile to load
+    int ld_i, ld_t;                // bitlayer and index of the next tile to load
+    uint32_t layer_bytes, wrap_bytes;
+    __amdgpu_buffer_rsrc_t rs_data, rs_null;
+};
+
+__device__ __forceinline__ void issue_tile_load(WaveCtx &c, uint2 &dst, int m)
 {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int slice = wave % a.csplit;
-    const int rw = wave / a.csplit;
-    const int n = blockIdx.y;
-    const int p = lane & 3, q = lane >> 2;
-    const int ws = a.ws, cwp = a.cwp, rpt = a.rpt, m = a.m;
+    dst = load_tile(c.ld_t < c.T ? c.rs_data : c.rs_null, c.voff, (int)c.soff);
+    __builtin_amdgcn_sched_barrier(0x7);  // loads return in issue order: keep it the order of use
+    ++c.ld_t;
+    if (++c.ld_i == m) { c.ld_i = 0; c.soff += c.wrap_bytes; } else c.soff += c.layer_bytes;
+}
+
+// Planes of the wave's slice: lane (q, p) holds, for pass t, the 8 words of plane 4t + p that face its quad.
+__device__ __forceinline__ void load_planes(const MatvecArgs &a, const WaveCtx &c, int t, uint32_t (&dst)[8])
+{
+    const int p = c.lane & 3, q = c.lane >> 2;
+    const uint32_t *pl = a.planes + (size_t)c.n * 32 * (size_t)a.cwp;
+    const int seg = c.slice * a.ws + ((q * 8) & (a.ws - 1));
+    const uint4 *src = reinterpret_cast<const uint4 *>(pl + (size_t)(4 * t + p) * a.cwp + seg);
+    uint4 v0 = src[0], v1 = src[1];
+    dst[0] = v0.x; dst[1] = v0.y; dst[2] = v0.z; dst[3] = v0.w;
+    dst[4] = v1.x; dst[5] = v1.y; dst[6] = v1.z; dst[7] = v1.w;
+}
+
+template <int NPASS, bool EARLY>
+__device__ __forceinline__ void matvec_body(const MatvecArgs &a, WaveCtx &c, uint2 (&buf)[kRing], const int h,
+                                            const float scv, const uint32_t (&pr_all)[8][8], char *smem)
+{
+    const int lane = c.lane, wave = c.wave, slice = c.slice, n = c.n;
+    const int p = lane & 3;
+    const int rpt = a.rpt, m = a.m;
+    const int T = c.T, gbase = c.gbase, gcount = c.gcount;
 
     // LDS: per wave [kRing tiles][64 lanes] (lo, hi) pairs, then the int64 results of all waves
     int2 *red = reinterpret_cast<int2 *>(smem) + (size_t)wave * kRing * 64;
     long long *abuf_all = reinterpret_cast<long long *>(smem + (size_t)blockDim.x / 64 * kRing * 64 * sizeof(int2));
     long long *abuf = abuf_all + (size_t)wave * a.abuf_words;
 
-    // --- planes of this wave's slice into registers; per-lane plane weights ---
-    const int *mt = a.meta + (size_t)n * kMetaInts;
-    const int h = mt[0];
-    const uint32_t *pl = a.planes + (size_t)n * 32 * (size_t)cwp;
-    const int seg = slice * ws + ((q * 8) & (ws - 1));
+    // --- planes of this wave's slice in registers; per-lane plane weights ---
     uint32_t pr[NPASS][8];
 #pragma unroll
     for (int t = 0; t < NPASS; ++t) {
-        const uint4 *src = reinterpret_cast<const uint4 *>(pl + (size_t)(4 * t + p) * cwp + seg);
-        uint4 v0 = src[0], v1 = src[1];
-        pr[t][0] = v0.x; pr[t][1] = v0.y; pr[t][2] = v0.z; pr[t][3] = v0.w;
-        pr[t][4] = v1.x; pr[t][5] = v1.y; pr[t][6] = v1.z; pr[t][7] = v1.w;
+        if (EARLY) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pr[t][i] = pr_all[t][i];
+        } else {
+            load_planes(a, c, t, pr[t]);
+        }
     }
+    if (!EARLY) __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): planes (and the tiles issued before them) have landed
     int mult[8];
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
         int j = 4 * t + p;
         int wgt = 1 << (j & 15);
         mult[t] = (j < h) ? wgt : (j == h ? -wgt : 0);
-    }
-
-    // --- this wave's tiles: row groups [gbase, gbase + gcount), bitlayers [0, m) ---
-    const int gbase = (blockIdx.x * a.rwaves + rw) * a.gw;
-    int gcount = a.num_rowgroups - gbase;
-    gcount = gcount < 0 ? 0 : (gcount > a.gw ? a.gw : gcount);
-    const int T = gcount * m;
-    const int voff = (int)(((lane * 2) / ws) * cwp + slice * ws + ((lane * 2) & (ws - 1))) * 4;
-    const size_t rg_bytes = (size_t)rpt * (size_t)cwp * 4;
-    const size_t base_off = (size_t)gbase * rg_bytes;
-    const size_t avail = a.packed_bytes > base_off ? a.packed_bytes - base_off : 0;
-    const __amdgpu_buffer_rsrc_t rs_data = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<char *>(reinterpret_cast<const char *>(a.packed) + base_off), 0,
-        (int)(avail > 0xFFFFFFFFull ? 0xFFFFFFFFull : avail), 0x00020000);
-    const __amdgpu_buffer_rsrc_t rs_null =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.packed), 0, 0, 0x00020000);
-    const uint32_t layer_bytes = (uint32_t)(a.layer_words * 4);
-    const uint32_t wrap_bytes = (uint32_t)rg_bytes - (uint32_t)(m - 1) * layer_bytes;  // last layer -> next row group
-
-    uint2 buf[kRing];
-    uint32_t soff = 0;  // byte offset of the next tile to load, relative to the wave's first tile
-    int ld_i = 0, ld_t = 0;
-#pragma unroll
-    for (int u = 0; u < kRing; ++u) {
-        buf[u] = load_tile(ld_t < T ? rs_data : rs_null, voff, (int)soff);
-        __builtin_amdgcn_sched_barrier(0x7);  // loads return in issue order: keep it the order of use
-        ++ld_t;
-        if (++ld_i == m) { ld_i = 0; soff += wrap_bytes; } else soff += layer_bytes;
     }
 
     // mapping of the deferred cross-lane sums: kRing * rpt outputs, 4 / rpt lanes each, 16 partials per lane
@@ -185,10 +186,7 @@ __device__ __forceinline__ void matvec_body(const MatvecArgs &a, char *smem)
                 red[u * 64 + lane] = make_int2(lo, hi);
             }
             // the ring slot is free again: fetch the tile kRing ahead (a no-op load past the end)
-            buf[u] = load_tile(ld_t < T ? rs_data : rs_null, voff, (int)soff);
-            __builtin_amdgcn_sched_barrier(0x7);
-            ++ld_t;
-            if (++ld_i == m) { ld_i = 0; soff += wrap_bytes; } else soff += layer_bytes;
+            issue_tile_load(c, buf[u], m);
         }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
@@ -222,36 +220,88 @@ __device__ __forceinline__ void matvec_body(const MatvecArgs &a, char *smem)
     if (a.csplit > 1) __syncthreads();
     if (slice == 0) {
         const int nout = gcount * rpt;
-        for (int idx = lane; idx < nout; idx += 64) {
+        for (int idx0 = 0; idx0 < nout; idx0 += 64) {
+            const int idx = idx0 + lane;
             const int gl = idx / rpt, rr = idx - gl * rpt;
             const int row = (gbase + gl) * rpt + rr;
-            if (row >= a.R) continue;
+            const bool valid = idx < nout && row < a.R;
             double z = 0.0;
-            for (int i = 0; i < m; ++i) {
-                long long v = 0;
-                for (int s = 0; s < a.csplit; ++s) v += abuf[(size_t)s * a.abuf_words + (gl * m + i) * rpt + rr];
-                if (a.A) a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] = v;
-                else z += (double)a.scales[i] * (double)v;
+#pragma unroll
+            for (int i = 0; i < PB_MAX_BITS; ++i) {
+                if (i < m) {
+                    const float si = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(scv), i));
+                    if (valid) {
+                        long long v = 0;
+                        for (int s = 0; s < a.csplit; ++s)
+                            v += abuf[(size_t)s * a.abuf_words + (gl * m + i) * rpt + rr];
+                        if (a.A) a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] = v;
+                        else z += (double)si * (double)v;
+                    }
+                }
             }
-            if (!a.A) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
+            if (valid && !a.A) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
         }
     }
 }
 
+// EARLY = fetch the planes of all 8 passes before anything else (no wait for the plane statistics; more cache
+// traffic); otherwise only the passes in use are fetched, after the statistics arrive.
+template <bool EARLY>
 __global__ __launch_bounds__(512) void k_matvec(const MatvecArgs a)
 {
     extern __shared__ __align__(16) char smem[];
-    const int npass = a.meta[(size_t)blockIdx.y * kMetaInts + 2];
+    WaveCtx c;
+    c.lane = threadIdx.x & 63;
+    c.wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    c.slice = c.wave % a.csplit;
+    c.rw = c.wave / a.csplit;
+    c.n = blockIdx.y;
+    const int m = a.m;
+
+    // scalar loads first: plane statistics and layer scales are needed late, their latency hides behind the tiles
+    const int *mt = a.meta + (size_t)c.n * kMetaInts;
+    const int h = mt[0];
+    const int npass = mt[2];
+    const float scv = a.scales ? a.scales[c.lane < m ? c.lane : m - 1] : 0.0f;  // lane i holds scales[i]
+
+    // this wave's tiles: row groups [gbase, gbase + gcount), bitlayers [0, m); start the weight stream at once
+    c.gbase = (blockIdx.x * a.rwaves + c.rw) * a.gw;
+    int gcount = a.num_rowgroups - c.gbase;
+    c.gcount = gcount < 0 ? 0 : (gcount > a.gw ? a.gw : gcount);
+    c.T = c.gcount * m;
+    c.voff = (int)(((c.lane * 2) / a.ws) * a.cwp + c.slice * a.ws + ((c.lane * 2) & (a.ws - 1))) * 4;
+    const size_t rg_bytes = (size_t)a.rpt * (size_t)a.cwp * 4;
+    const size_t base_off = (size_t)c.gbase * rg_bytes;
+    const size_t avail = a.packed_bytes > base_off ? a.packed_bytes - base_off : 0;
+    c.rs_data = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<char *>(reinterpret_cast<const char *>(a.packed) + base_off), 0,
+        (int)(avail > 0xFFFFFFFFull ? 0xFFFFFFFFull : avail), 0x00020000);
+    c.rs_null = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t *>(a.packed), 0, 0, 0x00020000);
+    c.layer_bytes = (uint32_t)(a.layer_words * 4);
+    c.wrap_bytes = (uint32_t)rg_bytes - (uint32_t)(m - 1) * c.layer_bytes;  // last layer -> next row group
+    c.soff = 0;
+    c.ld_i = 0;
+    c.ld_t = 0;
+    uint32_t pr_all[8][8];
+    if (EARLY) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) load_planes(a, c, t, pr_all[t]);
+        __builtin_amdgcn_sched_barrier(0x7);
+    }
+    uint2 buf[kRing];
+#pragma unroll
+    for (int u = 0; u < kRing; ++u) issue_tile_load(c, buf[u], m);
+
     switch (npass) {
-        case 0: matvec_body<1>(a, smem); break;  // all-zero activations: the one pass has zero weights
-        case 1: matvec_body<1>(a, smem); break;
-        case 2: matvec_body<2>(a, smem); break;
-        case 3: matvec_body<3>(a, smem); break;
-        case 4: matvec_body<4>(a, smem); break;
-        case 5: matvec_body<5>(a, smem); break;
-        case 6: matvec_body<6>(a, smem); break;
-        case 7: matvec_body<7>(a, smem); break;
-        default: matvec_body<8>(a, smem); break;
+        case 0: matvec_body<1, EARLY>(a, c, buf, h, scv, pr_all, smem); break;  // all-zero activations: the one pass weighs 0
+        case 1: matvec_body<1, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        case 2: matvec_body<2, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        case 3: matvec_body<3, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        case 4: matvec_body<4, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        case 5: matvec_body<5, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        case 6: matvec_body<6, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        case 7: matvec_body<7, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
+        default: matvec_body<8, EARLY>(a, c, buf, h, scv, pr_all, smem); break;
     }
 }
 
@@ -264,13 +314,17 @@ int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, 
     a.packed_bytes = packed_bytes(L);
     a.R = L.rows; a.cwp = L.cwp; a.ws = L.ws; a.rpt = L.rpt; a.csplit = L.csplit;
     a.rwaves = L.csplit == 1 ? 4 : (L.csplit == 2 ? 2 : (L.csplit <= 4 ? 2 : 1));
+    int target_wgs = 512;
+    bool early = false;
+    if (const char *e = getenv("PB_TUNE_RWAVES")) a.rwaves = atoi(e);
+    if (const char *e = getenv("PB_TUNE_WGS")) target_wgs = atoi(e);
+    if (const char *e = getenv("PB_TUNE_EARLY")) early = atoi(e) != 0;
     if (a.csplit * a.rwaves > kMaxWavesPerWG) a.rwaves = 1;
     a.m = bits_used;
     a.num_rowgroups = L.rows_p / L.rpt;
     a.batch = batch;
     a.out_scale = ldexp(1.0, -frac_bits);
     // row groups per wave: aim at >= 2 workgroups per CU, bounded LDS result buffer
-    const int target_wgs = 512;
     long long per_wg = ((long long)a.num_rowgroups + target_wgs - 1) / target_wgs;
     int gw = (int)((per_wg + a.rwaves - 1) / a.rwaves);
     if (gw < 1) gw = 1;
@@ -282,13 +336,14 @@ int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, 
     const int waves = a.csplit * a.rwaves;
     long long nwg = ((long long)a.num_rowgroups + (long long)gw * a.rwaves - 1) / ((long long)gw * a.rwaves);
     size_t smem = (size_t)waves * kRing * 64 * sizeof(int2) + (size_t)waves * a.abuf_words * sizeof(long long);
+    auto kern = early ? k_matvec<true> : k_matvec<false>;
     if (smem > 64 * 1024) {
         // more than the default 64 KB of dynamic LDS (a CU of this GPU has 160 KB)
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(k_matvec),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
         if (e != hipSuccess) return (int)e;
     }
-    hipLaunchKernelGGL(k_matvec, dim3((unsigned)nwg, (unsigned)batch), dim3(waves * 64), smem, st, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)nwg, (unsigned)batch), dim3(waves * 64), smem, st, a);
     return (int)hipGetLastError();
 }
 

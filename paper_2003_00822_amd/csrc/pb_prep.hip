@@ -2,13 +2,17 @@
 // Section 3.3: "a multiplication and a cast"; Section 3.4: the bitwise matrix
 // transpose that lays the bits of one plane next to each other for AND/popcount).
 //
-// One workgroup per activation vector.  A thread owns 32 consecutive columns:
-// it converts them to fixed point and transposes the 32x32 bit matrix in
-// registers, which yields one packed word of each of the 32 planes.  The
-// workgroup also reduces the plane statistics that let the product kernel skip
-// planes that carry no information: h = number of magnitude bits in use (planes
-// h..31 all equal the sign plane, so together they weigh -2^h), and whether any
-// value is negative.  Skipping them changes no result bit.
+// A workgroup of 4 waves owns 256 consecutive columns of one activation vector, a
+// lane one column.  The transpose is the wave64 ballot: bit j of the 64 lanes'
+// fixed-point values IS two packed words of plane j; v_writelane hands ballot j to
+// lane j, which stores it.  32 columns groups of a vector run in parallel on
+// different CUs, so the step is launch-latency bound, not compute bound.
+// Every workgroup also converts the whole vector once (it is a few KB, coalesced)
+// to reduce the plane statistics that let the product kernel skip planes carrying
+// no information: h = number of magnitude bits in use (planes h..31 all equal the
+// sign plane and together weigh -2^h) and whether any value is negative.  Doing
+// that per workgroup avoids any cross-workgroup reduction or second launch;
+// skipping those planes changes no result bit.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -25,71 +29,73 @@ __device__ __forceinline__ int32_t to_fixed(float p, float lim /* 2^(k-1) */, in
     return (int32_t)p;
 }
 
-// In-register transpose of a 32x32 bit matrix: on return bit b of a[j] is what bit j of a[b] was.
-__device__ __forceinline__ void transpose32(uint32_t (&a)[32])
-{
-#pragma unroll
-    for (int j = 16; j != 0; j >>= 1) {
-        // m selects, in every group of 2j bits, the low j bits
-        uint32_t m = 0xFFFFFFFFu / ((1u << j) + 1u);
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            if ((k & j) == 0) {
-                uint32_t t = ((a[k] >> j) ^ a[k + j]) & m;
-                a[k] ^= t << j;
-                a[k + j] ^= t;
-            }
-        }
-    }
-}
-
 __global__ __launch_bounds__(256) void k_prep(const float *__restrict__ X0, int cols0, const float *__restrict__ X1,
-                                              int cols1, int cw, int cwp, float fscale, float lim, int32_t imax,
+                                              int cols1, int cwp, float fscale, float lim, int32_t imax,
                                               int32_t imin, uint32_t *__restrict__ planes, int *__restrict__ meta,
                                               int32_t *__restrict__ xq_out)
 {
     __shared__ uint32_t s_mag, s_any;
-    const int n = blockIdx.x;
+    const int n = blockIdx.y;
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
     const int C = cols0 + cols1;
-    if (threadIdx.x == 0) { s_mag = 0; s_any = 0; }
+    if (tid == 0) { s_mag = 0; s_any = 0; }
     __syncthreads();
     const float *x0 = X0 + (size_t)n * cols0;
     const float *x1 = X1 ? X1 + (size_t)n * cols1 : nullptr;
-    uint32_t *pl = planes + (size_t)n * 32 * (size_t)cwp;
+
+    // whole vector, 256 columns at a time: statistics; chunk b holds this lane's own column
     uint32_t mag = 0, any = 0;
-    for (int w = threadIdx.x; w < cwp; w += blockDim.x) {
-        uint32_t a[32];
-#pragma unroll
-        for (int b = 0; b < 32; ++b) {
-            int c = w * 32 + b;
-            float v = 0.0f;
-            if (c < cols0) v = x0[c];
-            else if (c < C) v = x1[c - cols0];
-            int32_t xq = to_fixed(v * fscale, lim, imax, imin);
-            if (xq_out && c < C) xq_out[(size_t)n * C + c] = xq;
-            a[b] = (uint32_t)xq;
-            mag |= (uint32_t)(xq ^ (xq >> 31));
-            any |= (uint32_t)xq;
-        }
-        transpose32(a);
-#pragma unroll
-        for (int j = 0; j < 32; ++j) pl[(size_t)j * cwp + w] = a[j];
+    int32_t mine = 0;
+    const int chunks = (C + 255) >> 8;
+    for (int k = 0; k < chunks; ++k) {
+        const int c = (k << 8) + tid;
+        float v = 0.0f;
+        if (c < cols0) v = x0[c];
+        else if (c < C) v = x1[c - cols0];
+        const int32_t xq = to_fixed(v * fscale, lim, imax, imin);
+        mag |= (uint32_t)(xq ^ (xq >> 31));
+        any |= (uint32_t)xq;
+        if (k == b) mine = xq;
     }
+    const int c_own = (b << 8) + tid;
+    if (xq_out && c_own < C) xq_out[(size_t)n * C + c_own] = mine;
+
+    // bitwise transpose of this wave's 64 columns: ballot j = words (2g, 2g+1) of plane j
+    uint32_t lo = 0, hi = 0;
+#define PB_PLANE(J)                                                                                   \
+    {                                                                                                 \
+        const unsigned long long bal = __ballot((mine >> (J)) & 1);                                   \
+        asm("v_writelane_b32 %0, %1, " #J : "+v"(lo) : "s"((uint32_t)bal));                           \
+        asm("v_writelane_b32 %0, %1, " #J : "+v"(hi) : "s"((uint32_t)(bal >> 32)));                   \
+    }
+    PB_PLANE(0) PB_PLANE(1) PB_PLANE(2) PB_PLANE(3) PB_PLANE(4) PB_PLANE(5) PB_PLANE(6) PB_PLANE(7)
+    PB_PLANE(8) PB_PLANE(9) PB_PLANE(10) PB_PLANE(11) PB_PLANE(12) PB_PLANE(13) PB_PLANE(14) PB_PLANE(15)
+    PB_PLANE(16) PB_PLANE(17) PB_PLANE(18) PB_PLANE(19) PB_PLANE(20) PB_PLANE(21) PB_PLANE(22) PB_PLANE(23)
+    PB_PLANE(24) PB_PLANE(25) PB_PLANE(26) PB_PLANE(27) PB_PLANE(28) PB_PLANE(29) PB_PLANE(30) PB_PLANE(31)
+#undef PB_PLANE
+    const int word0 = 2 * (4 * b + wave);
+    if (lane < 32 && word0 < cwp) {
+        uint32_t *dst = planes + ((size_t)n * 32 + lane) * (size_t)cwp + word0;
+        *reinterpret_cast<uint2 *>(dst) = make_uint2(lo, hi);
+    }
+
     for (int off = 32; off > 0; off >>= 1) {
         mag |= (uint32_t)__shfl_xor((int)mag, off, 64);
         any |= (uint32_t)__shfl_xor((int)any, off, 64);
     }
-    if ((threadIdx.x & 63) == 0) { atomicOr(&s_mag, mag); atomicOr(&s_any, any); }
+    if (lane == 0) { atomicOr(&s_mag, mag); atomicOr(&s_any, any); }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        uint32_t mg = s_mag;
-        int h = mg ? 32 - __clz((int)mg) : 0;   // magnitude planes 0..h-1; plane h is the sign plane
-        int neg = (int)(s_any >> 31);
-        int nplanes = neg ? h + 1 : h;          // planes that must be multiplied
+    if (b == 0 && tid == 0) {
+        const uint32_t mg = s_mag;
+        const int h = mg ? 32 - __clz((int)mg) : 0;   // magnitude planes 0..h-1; plane h is the sign plane
+        const int neg = (int)(s_any >> 31);
+        const int nplanes = neg ? h + 1 : h;          // planes that must be multiplied
         int *mt = meta + (size_t)n * kMetaInts;
         mt[0] = h;
         mt[1] = neg;
-        mt[2] = (nplanes + 3) >> 2;             // passes of 4 planes
+        mt[2] = (nplanes + 3) >> 2;                   // passes of 4 planes
         mt[3] = nplanes;
     }
 }
@@ -101,8 +107,8 @@ int launch_prep(const float *X0, int cols0, const float *X1, int cols1, int batc
     float lim = ldexpf(1.0f, act_bits - 1);
     int32_t imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
     int32_t imin = (act_bits == 32) ? INT32_MIN : -(int32_t)(1u << (act_bits - 1));
-    hipLaunchKernelGGL(k_prep, dim3(batch), dim3(256), 0, st, X0, cols0, X1, cols1, L.cw, L.cwp, fscale, lim, imax,
-                       imin, planes, meta, xq_out);
+    hipLaunchKernelGGL(k_prep, dim3(L.cwp / 8, batch), dim3(256), 0, st, X0, cols0, X1, cols1, L.cwp, fscale, lim,
+                       imax, imin, planes, meta, xq_out);
     return (int)hipGetLastError();
 }
 
