@@ -16,7 +16,7 @@ namespace pb {
 
 constexpr int kWave = 64;
 constexpr int kTileWords = 128;     // one matvec tile: 64 lanes x 2 words
-constexpr int kRing = 16;           // tiles in flight per wave
+constexpr int kRing = 8;            // weight tiles in flight per wave
 constexpr int kMaxWavesPerWG = 8;
 constexpr int kMetaInts = 16;       // per activation vector, in the workspace
 

@@ -4,8 +4,8 @@
 //
 // A workgroup of 4 waves owns 256 consecutive columns of one activation vector, a
 // lane one column.  The transpose is the wave64 ballot: bit j of the 64 lanes'
-// fixed-point values IS two packed words of plane j; v_writelane hands ballot j to
-// lane j, which stores it.  32 columns groups of a vector run in parallel on
+// fixed-point values IS two packed words of plane j; lane j keeps ballot j and
+// stores it.  32 columns groups of a vector run in parallel on
 // different CUs, so the step is launch-latency bound, not compute bound.
 // Every workgroup also converts the whole vector once (it is a few KB, coalesced)
 // to reduce the plane statistics that let the product kernel skip planes carrying
@@ -20,18 +20,20 @@
 
 namespace pb {
 
-// k-bit saturating, toward-zero conversion of p = x * 2^f; NaN -> 0.
-__device__ __forceinline__ int32_t to_fixed(float p, float lim /* 2^(k-1) */, int32_t imax, int32_t imin)
+// k-bit saturating, toward-zero conversion of p = x * 2^f; NaN -> 0.  lim = 2^(k-1), lim_below = the largest
+// float below it.  Branch-free: clamp into the range where the cast is defined, then patch the top end and NaN
+// (the bottom end, -2^(k-1), converts exactly).
+__device__ __forceinline__ int32_t to_fixed(float p, float lim, float lim_below, int32_t imax)
 {
-    if (p != p) return 0;
-    if (p >= lim) return imax;
-    if (p <= -lim) return imin;
-    return (int32_t)p;
+    const float pc = fminf(fmaxf(p, -lim), lim_below);
+    int32_t r = (int32_t)pc;
+    r = (p >= lim) ? imax : r;
+    return (p != p) ? 0 : r;
 }
 
 __global__ __launch_bounds__(256) void k_prep(const float *__restrict__ X0, int cols0, const float *__restrict__ X1,
-                                              int cols1, int cwp, float fscale, float lim, int32_t imax,
-                                              int32_t imin, uint32_t *__restrict__ planes, int *__restrict__ meta,
+                                              int cols1, int cwp, float fscale, float lim, float lim_below,
+                                              int32_t imax, uint32_t *__restrict__ planes, int *__restrict__ meta,
                                               int32_t *__restrict__ xq_out)
 {
     __shared__ uint32_t s_mag, s_any;
@@ -45,36 +47,41 @@ __global__ __launch_bounds__(256) void k_prep(const float *__restrict__ X0, int 
     const float *x0 = X0 + (size_t)n * cols0;
     const float *x1 = X1 ? X1 + (size_t)n * cols1 : nullptr;
 
-    // whole vector, 256 columns at a time: statistics; chunk b holds this lane's own column
-    uint32_t mag = 0, any = 0;
-    int32_t mine = 0;
-    const int chunks = (C + 255) >> 8;
-    for (int k = 0; k < chunks; ++k) {
-        const int c = (k << 8) + tid;
+    auto fetch = [&](int c) -> float {
         float v = 0.0f;
         if (c < cols0) v = x0[c];
         else if (c < C) v = x1[c - cols0];
-        const int32_t xq = to_fixed(v * fscale, lim, imax, imin);
-        mag |= (uint32_t)(xq ^ (xq >> 31));
-        any |= (uint32_t)xq;
-        if (k == b) mine = xq;
+        return v;
+    };
+    // this lane's own column first, then the whole vector, 8 x 256 columns at a time (independent loads in flight)
+    const float v_own = fetch((b << 8) + tid);
+    uint32_t mag = 0, any = 0;
+    const int chunks = (C + 255) >> 8;
+    for (int k0 = 0; k0 < chunks; k0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) v[j] = fetch(((k0 + j) << 8) + tid);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int32_t xq = to_fixed(v[j] * fscale, lim, lim_below, imax);
+            mag |= (uint32_t)(xq ^ (xq >> 31));
+            any |= (uint32_t)xq;
+        }
     }
+    const int32_t mine = to_fixed(v_own * fscale, lim, lim_below, imax);
     const int c_own = (b << 8) + tid;
     if (xq_out && c_own < C) xq_out[(size_t)n * C + c_own] = mine;
 
     // bitwise transpose of this wave's 64 columns: ballot j = words (2g, 2g+1) of plane j
+    // (a select per plane rather than v_writelane: the compiler then inserts the wait states that a VALU-written
+    // SGPR needs before a lane-indexed write reads it)
     uint32_t lo = 0, hi = 0;
-#define PB_PLANE(J)                                                                                   \
-    {                                                                                                 \
-        const unsigned long long bal = __ballot((mine >> (J)) & 1);                                   \
-        asm("v_writelane_b32 %0, %1, " #J : "+v"(lo) : "s"((uint32_t)bal));                           \
-        asm("v_writelane_b32 %0, %1, " #J : "+v"(hi) : "s"((uint32_t)(bal >> 32)));                   \
+#pragma unroll
+    for (int j = 0; j < 32; ++j) {
+        const unsigned long long bal = __ballot((mine >> j) & 1);
+        lo = (lane == j) ? (uint32_t)bal : lo;
+        hi = (lane == j) ? (uint32_t)(bal >> 32) : hi;
     }
-    PB_PLANE(0) PB_PLANE(1) PB_PLANE(2) PB_PLANE(3) PB_PLANE(4) PB_PLANE(5) PB_PLANE(6) PB_PLANE(7)
-    PB_PLANE(8) PB_PLANE(9) PB_PLANE(10) PB_PLANE(11) PB_PLANE(12) PB_PLANE(13) PB_PLANE(14) PB_PLANE(15)
-    PB_PLANE(16) PB_PLANE(17) PB_PLANE(18) PB_PLANE(19) PB_PLANE(20) PB_PLANE(21) PB_PLANE(22) PB_PLANE(23)
-    PB_PLANE(24) PB_PLANE(25) PB_PLANE(26) PB_PLANE(27) PB_PLANE(28) PB_PLANE(29) PB_PLANE(30) PB_PLANE(31)
-#undef PB_PLANE
     const int word0 = 2 * (4 * b + wave);
     if (lane < 32 && word0 < cwp) {
         uint32_t *dst = planes + ((size_t)n * 32 + lane) * (size_t)cwp + word0;
@@ -106,9 +113,9 @@ int launch_prep(const float *X0, int cols0, const float *X1, int cols1, int batc
     float fscale = ldexpf(1.0f, frac_bits);
     float lim = ldexpf(1.0f, act_bits - 1);
     int32_t imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
-    int32_t imin = (act_bits == 32) ? INT32_MIN : -(int32_t)(1u << (act_bits - 1));
+    float lim_below = nextafterf(lim, 0.0f);
     hipLaunchKernelGGL(k_prep, dim3(L.cwp / 8, batch), dim3(256), 0, st, X0, cols0, X1, cols1, L.cwp, fscale, lim,
-                       imax, imin, planes, meta, xq_out);
+                       lim_below, imax, planes, meta, xq_out);
     return (int)hipGetLastError();
 }
 
