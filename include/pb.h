@@ -48,7 +48,15 @@ typedef enum pb_status {
 #define PB_MAX_BITS 16       /* stored bitlayers B, 1..16 (Section 1: "1-16 bit execution") */
 #define PB_MAX_COLS 32768    /* columns of one weight matrix */
 #define PB_MAX_BATCH 4096    /* activation vectors per call */
+
+/* Packed layouts (opaque to the caller; pb_unpack reads either).
+ * PB_LAYOUT_TILE16_V1   16-row x 512-column blocks in the order the matrix-core kernel streams them; the
+ *                       default wherever it applies (cols <= 16384).  The product runs as FP4 matrix
+ *                       instructions on the 0/1 bitlayers and planes, exact in fp32 accumulators.
+ * PB_LAYOUT_ROWMAJOR_V1 [bitlayer][row][word]; read by the AND + popcount kernel (Section 3.4 taken
+ *                       literally), kept as the measured alternative and for cols up to PB_MAX_COLS. */
 #define PB_LAYOUT_ROWMAJOR_V1 0x50420001u
+#define PB_LAYOUT_TILE16_V1 0x50420002u
 
 /* Shape and format of one packed weight matrix (host struct, plain data).
  * bits      B, the number of stored bitlayers = two's-complement width of the
@@ -66,8 +74,12 @@ typedef struct pb_desc {
 } pb_desc;
 
 /* Fill *d (host) for a rows x cols matrix with `bits` bitlayers and the
- * defaults f = 16, k = 32.  PB_EINVAL / PB_ESIZE on bad shapes. */
+ * defaults f = 16, k = 32.  pb_desc_init picks the layout of the fastest kernel
+ * for the shape (PB_LAYOUT_TILE16_V1 up to 16384 columns, else
+ * PB_LAYOUT_ROWMAJOR_V1); pb_desc_init_layout takes it from the caller.
+ * PB_EINVAL / PB_ESIZE on bad shapes or a layout that does not fit the shape. */
 int pb_desc_init(pb_desc *d, int rows, int cols, int bits);
+int pb_desc_init_layout(pb_desc *d, int rows, int cols, int bits, uint32_t layout);
 
 /* Bytes the caller must allocate for `packed` (all B bitlayers, padded),
  * and for `workspace` of a call with `batch` activation vectors (bit planes,
@@ -88,6 +100,11 @@ size_t pb_workspace_bytes(const pb_desc *d, int batch);
  * Launches a few kernels on `stream`; nothing is returned to the host. */
 int pb_quantize_pack(const float *W, int rows, int cols, int bits, void *packed, float *scales, void *stream);
 
+/* The same for a descriptor the caller filled (pb_desc_init_layout): packs into
+ * d->layout.  pb_quantize_pack(W, rows, cols, bits, ...) is this call on the
+ * descriptor pb_desc_init(rows, cols, bits) gives. */
+int pb_quantize_pack_desc(const float *W, const pb_desc *d, void *packed, float *scales, void *stream);
+
 /* Inverse of the packing, for checking: q[r][c] = the B-bit code stored for
  * element (r, c), sign-extended to int32.  q: [rows][cols], written. */
 int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);
@@ -95,7 +112,8 @@ int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);
 /* Algorithm 2 (inference).  For each of the `batch` activation vectors:
  *   x_q = trunc(x * 2^f) as a k-bit two's-complement integer (saturating;
  *   NaN -> 0), split into k bit planes with weights 2^j and -2^(k-1);
- *   A_i[r] = sum_j c_j * popcount(row r of bitlayer i AND plane j)  (exact, int64)
+ *   A_i[r] = sum_j c_j * popcount(row r of bitlayer i AND plane j)  (exact, int64; computed as
+ *            AND + popcount or as an exact 0/1 matrix product, depending on the layout)
  *   Y[r]   = fp32( sum_{i < bits_used} scales[i] * A_i[r] * 2^-f )  (sum in fp64)
  * Only the first `bits_used` bitlayers (sign layer and the next bits_used-1)
  * are read: the accuracy / speed knob of the abstract.

@@ -19,9 +19,9 @@ int check_desc(const pb_desc *d, pb::Layout *L)
     if (d->rows < 1 || d->cols < 1 || d->bits < 1 || d->bits > PB_MAX_BITS) return PB_EINVAL;
     if (d->frac_bits < 0 || d->frac_bits > 30) return PB_EINVAL;
     if (d->act_bits < 2 || d->act_bits > 32) return PB_EINVAL;
-    if (d->layout != PB_LAYOUT_ROWMAJOR_V1) return PB_EINVAL;
+    if (d->layout != PB_LAYOUT_ROWMAJOR_V1 && d->layout != PB_LAYOUT_TILE16_V1) return PB_EINVAL;
     if (d->cols > PB_MAX_COLS) return PB_ESIZE;
-    if (!pb::make_layout(d->rows, d->cols, d->bits, L)) return PB_ESIZE;
+    if (!pb::make_layout(d->layout, d->rows, d->cols, d->bits, L)) return PB_ESIZE;
     if (pb::packed_bytes(*L) > 0xFFFFFFFFull) return PB_ESIZE;  // tiles are addressed with 32-bit byte offsets
     return PB_OK;
 }
@@ -37,7 +37,7 @@ int hip_status(int err)
 
 extern "C" {
 
-int pb_desc_init(pb_desc *d, int rows, int cols, int bits)
+int pb_desc_init_layout(pb_desc *d, int rows, int cols, int bits, uint32_t layout)
 {
     if (!d) return PB_EINVAL;
     if (rows < 1 || cols < 1 || bits < 1 || bits > PB_MAX_BITS) return PB_EINVAL;
@@ -47,9 +47,15 @@ int pb_desc_init(pb_desc *d, int rows, int cols, int bits)
     d->bits = bits;
     d->frac_bits = 16;
     d->act_bits = 32;
-    d->layout = PB_LAYOUT_ROWMAJOR_V1;
+    d->layout = layout;
     pb::Layout L;
     return check_desc(d, &L);
+}
+
+int pb_desc_init(pb_desc *d, int rows, int cols, int bits)
+{
+    return pb_desc_init_layout(d, rows, cols, bits,
+                               cols <= pb::kMaxColsTile16 ? PB_LAYOUT_TILE16_V1 : PB_LAYOUT_ROWMAJOR_V1);
 }
 
 size_t pb_packed_bytes(const pb_desc *d)
@@ -66,17 +72,23 @@ size_t pb_workspace_bytes(const pb_desc *d, int batch)
     return pb::workspace_bytes(L, batch);
 }
 
+int pb_quantize_pack_desc(const float *W, const pb_desc *d, void *packed, float *scales, void *stream)
+{
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (!W || !packed || !scales) return PB_EINVAL;
+    if (!aligned16(W) || !aligned16(packed) || !aligned16(scales)) return PB_EALIGN;
+    return hip_status(pb::launch_quantize_pack(W, L, static_cast<uint32_t *>(packed), scales,
+                                               static_cast<hipStream_t>(stream)));
+}
+
 int pb_quantize_pack(const float *W, int rows, int cols, int bits, void *packed, float *scales, void *stream)
 {
     pb_desc d;
     int rc = pb_desc_init(&d, rows, cols, bits);
     if (rc != PB_OK) return rc;
-    if (!W || !packed || !scales) return PB_EINVAL;
-    if (!aligned16(W) || !aligned16(packed) || !aligned16(scales)) return PB_EALIGN;
-    pb::Layout L;
-    pb::make_layout(rows, cols, bits, &L);
-    return hip_status(pb::launch_quantize_pack(W, L, static_cast<uint32_t *>(packed), scales,
-                                               static_cast<hipStream_t>(stream)));
+    return pb_quantize_pack_desc(W, &d, packed, scales, stream);
 }
 
 int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream)
@@ -104,6 +116,10 @@ static int matmul_common(const void *packed, const float *scales, const pb_desc 
         (A && !aligned16(A)) || (scales && !aligned16(scales)) || (X1 && !aligned16(X1)))
         return PB_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
+    if (L.layout == PB_LAYOUT_TILE16_V1)   // conversion, bit transpose and product in one launch
+        return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
+                                          d->act_bits, X0, cols0, X1, cols1, nullptr, batch, Y,
+                                          reinterpret_cast<long long *>(A), st));
     char *ws = static_cast<char *>(workspace);
     int *meta = reinterpret_cast<int *>(ws + pb::ws_meta_off(L, batch));
     uint32_t *planes = reinterpret_cast<uint32_t *>(ws + pb::ws_planes_off(L, batch));
@@ -158,6 +174,10 @@ int pb_matmul_prepared(const void *packed, const float *scales, const pb_desc *d
     char *ws = static_cast<char *>(workspace);
     const int *meta = reinterpret_cast<const int *>(ws + pb::ws_meta_off(L, batch));
     const uint32_t *planes = reinterpret_cast<const uint32_t *>(ws + pb::ws_planes_off(L, batch));
+    if (L.layout == PB_LAYOUT_TILE16_V1)
+        return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
+                                          d->act_bits, nullptr, 0, nullptr, 0, planes, batch, Y, nullptr,
+                                          static_cast<hipStream_t>(stream)));
     return hip_status(pb::launch_matvec(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                         planes, meta, batch, Y, nullptr, static_cast<hipStream_t>(stream)));
 }

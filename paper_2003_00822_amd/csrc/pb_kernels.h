@@ -22,6 +22,13 @@ int launch_prep(const float *X0, int cols0, const float *X1, int cols1, int batc
 int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                   const uint32_t *planes, const int *meta, int batch, float *Y, long long *A, hipStream_t st);
 
+// pb_mfma.hip: the whole of Algorithm 2 in one launch on the matrix cores (PB_LAYOUT_TILE16_V1).  Activations come
+// from X0 / X1 (converted and bit-transposed inside the kernel) or, if `planes` is non-null, from bit planes that
+// launch_prep left in memory.  Exactly one of Y / A is non-null.
+int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
+                int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
+                int batch, float *Y, long long *A, hipStream_t st);
+
 // pb_lstm.hip: gate nonlinearities and state update on the gate pre-activations.
 int launch_lstm_pointwise(const float *gates, const float *bias, const float *c_prev, int H, int batch, float *h_out,
                           float *c_out, hipStream_t st);

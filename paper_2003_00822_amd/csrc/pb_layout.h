@@ -1,10 +1,20 @@
-// Internal: packed-weight layout and workspace carving shared by the host API
+// Internal: packed-weight layouts and workspace carving shared by the host API
 // and the kernels of this library (not part of the public ABI).
 //
-// Packed layout PB_LAYOUT_ROWMAJOR_V1: uint32 words, [bitlayer i][row r][word w],
-// bitlayer 0 = sign layer (Section 3.2 / Algorithm 1 of the paper), bit (c % 32)
-// of word c / 32 is the layer's bit for column c (Section 3.4: 32 values per
-// word).  Rows are padded to `rows_p` and words per row to `cwp`; padding is 0.
+// Both layouts store uint32 words of 32 columns each (Section 3.4 of the paper: 32
+// values per word), bit (c % 32) of word c / 32 is the layer's bit for column c,
+// bitlayer 0 = sign layer (Section 3.2 / Algorithm 1), one bitlayer after the other
+// (`layer_words` apart) so that the first `bits_used` layers are one contiguous
+// region.  Rows are padded to `rows_p` and words per row to `cwp`; padding is 0.
+//
+// PB_LAYOUT_ROWMAJOR_V1: [bitlayer][row][word].  Read by the AND + popcount kernel.
+//
+// PB_LAYOUT_TILE16_V1: [bitlayer][row tile of 16][chunk of 16 words][lane][4 words].
+//   A 1 KB block holds 16 rows x 16 words in the order a wave of the matrix-core
+//   kernel consumes it: lane l = 16 * kb + j (j = row in the tile, kb = 0..3) owns
+//   the 16 bytes at l * 16, the words 16 * chunk + 4 * kb + t (t = 0..3) of row j.
+//   One 16-byte load per lane fetches a whole block, fully coalesced, and word t of
+//   every lane is the B operand of one 16x16x128 matrix instruction (row j, k-block kb).
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -15,47 +25,79 @@
 namespace pb {
 
 constexpr int kWave = 64;
-constexpr int kTileWords = 128;     // one matvec tile: 64 lanes x 2 words
-constexpr int kRing = 8;            // weight tiles in flight per wave
-constexpr int kMaxWavesPerWG = 8;
+constexpr int kTileWords = 128;     // popcount kernel: one tile = 64 lanes x 2 words
+constexpr int kRing = 8;            // popcount kernel: weight tiles in flight per wave
+constexpr int kMaxWavesPerWG = 8;   // popcount kernel
 constexpr int kMetaInts = 16;       // per activation vector, in the workspace
 
+constexpr int kTileRows = 16;       // matrix-core kernel: rows per tile
+constexpr int kChunkWords = 16;     // matrix-core kernel: words per row in one block
+constexpr int kMaxSlices = 16;      // matrix-core kernel: waves (column slices) per workgroup
+constexpr int kMaxColsTile16 = 16384;
+
 struct Layout {
+    uint32_t layout;
     int rows, cols, bits;
     int cw;        // words that hold real columns: ceil(cols / 32)
+    int cwp;       // padded words per row
+    int rows_p;    // padded rows
+    size_t layer_words;  // rows_p * cwp
+    // PB_LAYOUT_ROWMAJOR_V1
     int ws;        // words of one row handled by one wave (32, 64 or 128)
     int csplit;    // waves that share a row: cwp = ws * csplit
-    int cwp;       // padded words per row
     int rpt;       // rows per tile = 128 / ws
-    int rows_p;    // rows padded to a multiple of 4
-    size_t layer_words;  // rows_p * cwp
+    // PB_LAYOUT_TILE16_V1
+    int rt_count;  // row tiles: rows_p / 16
+    int cq;        // chunks per row: cwp / 16
 };
 
-inline bool make_layout(int rows, int cols, int bits, Layout *L)
+inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L)
 {
     if (rows < 1 || cols < 1 || bits < 1 || bits > PB_MAX_BITS) return false;
     if (cols > PB_MAX_COLS) return false;
+    L->layout = layout;
     L->rows = rows; L->cols = cols; L->bits = bits;
     L->cw = (cols + 31) / 32;
-    int best_ws = 0, best_pad = 0;
-    const int cand[3] = {128, 64, 32};
-    const char *force = getenv("PB_TUNE_WS");
-    for (int k = 0; k < 3; ++k) {
-        int ws = cand[k];
-        if (force && atoi(force) != ws) continue;
-        int cs = (L->cw + ws - 1) / ws;
-        if (cs > kMaxWavesPerWG) continue;
-        int pad = cs * ws;
-        if (best_ws == 0 || pad < best_pad) { best_ws = ws; best_pad = pad; }
+    L->ws = L->csplit = L->rpt = L->rt_count = L->cq = 0;
+    if (layout == PB_LAYOUT_ROWMAJOR_V1) {
+        int best_ws = 0, best_pad = 0;
+        const int cand[3] = {128, 64, 32};
+        const char *force = getenv("PB_TUNE_WS");
+        for (int k = 0; k < 3; ++k) {
+            int ws = cand[k];
+            if (force && atoi(force) != ws) continue;
+            int cs = (L->cw + ws - 1) / ws;
+            if (cs > kMaxWavesPerWG) continue;
+            int pad = cs * ws;
+            if (best_ws == 0 || pad < best_pad) { best_ws = ws; best_pad = pad; }
+        }
+        if (best_ws == 0) return false;
+        L->ws = best_ws;
+        L->csplit = best_pad / best_ws;
+        L->cwp = best_pad;
+        L->rpt = kTileWords / best_ws;
+        L->rows_p = (rows + 3) & ~3;
+    } else if (layout == PB_LAYOUT_TILE16_V1) {
+        if (cols > kMaxColsTile16) return false;
+        L->cq = (L->cw + kChunkWords - 1) / kChunkWords;
+        L->cwp = L->cq * kChunkWords;
+        L->rt_count = (rows + kTileRows - 1) / kTileRows;
+        L->rows_p = L->rt_count * kTileRows;
+    } else {
+        return false;
     }
-    if (best_ws == 0) return false;
-    L->ws = best_ws;
-    L->csplit = best_pad / best_ws;
-    L->cwp = best_pad;
-    L->rpt = kTileWords / best_ws;
-    L->rows_p = (rows + 3) & ~3;
     L->layer_words = (size_t)L->rows_p * (size_t)L->cwp;
     return true;
+}
+
+// Position (in words, inside one bitlayer) of word w of row r.
+__host__ __device__ inline size_t word_index(uint32_t layout, int cwp, int r, int w)
+{
+    if (layout == PB_LAYOUT_ROWMAJOR_V1) return (size_t)r * (size_t)cwp + (size_t)w;
+    const int cq = cwp / kChunkWords;
+    const size_t block = (size_t)(r / kTileRows) * (size_t)cq + (size_t)(w / kChunkWords);
+    const int lane = ((w % kChunkWords) / 4) * kTileRows + (r % kTileRows);
+    return block * 256 + (size_t)lane * 4 + (size_t)(w % 4);
 }
 
 inline size_t packed_bytes(const Layout &L) { return L.layer_words * (size_t)L.bits * sizeof(uint32_t); }

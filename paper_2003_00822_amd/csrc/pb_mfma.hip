@@ -1,0 +1,360 @@
+// The hot kernel on the matrix cores: the whole inference path of Algorithm 2 of the
+// paper in one launch -- x_q = Int(x * 2^f), the bitwise transpose into bit planes
+// (Section 3.4), the 1-bit products of Section 3.1 with the 32 planes of a vector
+// batched as the second matrix operand ("one batched matrix product"), the plane
+// weights [-2^31, 2^30 .. 2^0] and the scale-accumulation over the first `bits_used`
+// bitlayers (the run-time knob of the abstract).
+//
+// Why the matrix cores: AND + popcount costs two vector-ALU lane operations per
+// (32-bit weight word, plane); with 32 planes that is four times what the ALUs of
+// this chip can do while HBM delivers the words.  The same 0/1 inner products are
+// a dense contraction with N = 32 planes, and V_MFMA_SCALE_F32_16X16X128_F8F6F4 on
+// FP4 (E2M1) operands does 32768 of them per instruction with exact results: the
+// products are 0 or 1 and the fp32 accumulators count to 2^24.
+//
+// Operands.  A (16 x 128) = 16 planes x 128 columns, B (128 x 16) = 128 columns x
+// 16 weight rows, D (16 x 16): lane l of D holds row j = l % 16 of the weights and
+// the planes 4 * (l / 16) + v in its four registers v, so the plane weighting is
+// arithmetic inside a lane.  Two instructions (planes 0-15 and 16-31) share one B.
+// A lane's B operand is 32 columns of one weight row = ONE packed word, expanded
+// from 1 bit to the 4-bit FP4 code per column with five ALU operations:
+//     b0 = w & 0x11111111 (0.5)   b1 = w & 0x22222222 (1.0)
+//     b2 = w & 0x44444444 (2.0)   b3 = (w >> 1) & 0x44444444 (2.0)
+// and the plane operand carries the matching codes 2.0, 1.0, 0.5, 0.5 so that every
+// product of two set bits is exactly 1.0.  Which column sits in which k slot does
+// not matter as long as both operands agree.
+//
+// Mapping.  A wave owns a slice of the columns (NQ chunks of 512) for its whole life
+// and keeps the expanded planes of that slice in registers; it streams the 1 KB
+// blocks of its slice (see pb_layout.h) for row tile after row tile and bitlayer
+// after bitlayer with 16-byte loads, several blocks in flight.  The waves of a
+// workgroup are the slices of one row; their per-(row, bitlayer) sums meet in LDS
+// through integer atomics, once per row tile, and one wave applies the layer scales
+// and stores.  All integer results are exact, so they do not depend on the schedule.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdlib.h>
+
+#include "pb_kernels.h"
+
+namespace pb {
+
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct MfmaArgs {
+    const uint32_t *packed;
+    const float *X0, *X1;       // activations: row n is [X0[n][0..cols0) ; X1[n][0..cols1)]
+    const uint32_t *planes;     // non-null: bit planes already in memory [batch][32][cwp] (prepared mode)
+    const float *scales;
+    float *Y;
+    long long *A;
+    size_t packed_bytes;
+    uint32_t layer_bytes;
+    int cols0, cols1;
+    int R, rt_count, cq, cwp;
+    int m;                      // bitlayers to accumulate
+    int batch;
+    int rounds_per_wg;          // row tiles per workgroup
+    float fscale, lim, lim_below;
+    int imax;
+    double out_scale;           // 2^-frac_bits
+};
+
+// k-bit saturating, toward-zero conversion of p = x * 2^f; NaN -> 0 (same rule as the stand-alone activation kernel)
+__device__ __forceinline__ int32_t to_fixed_point(float p, float lim, float lim_below, int32_t imax)
+{
+    const float pc = fminf(fmaxf(p, -lim), lim_below);
+    int32_t r = (int32_t)pc;
+    r = (p >= lim) ? imax : r;
+    return (p != p) ? 0 : r;
+}
+
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor(uint32_t v)
+{
+    // value of lane (l ^ J), inside each half of 32 lanes: ds_swizzle in bit-mask mode (and 0x1f, or 0, xor J)
+    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (J << 10));
+}
+
+// One stage of the 32 x 32 bit-matrix transpose across 32 lanes: rows l and l ^ J exchange the bit
+// positions that have bit J set (lower row) / clear (upper row).
+template <int J>
+__device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int lane)
+{
+    constexpr uint32_t M = J == 16 ? 0xFFFF0000u : J == 8 ? 0xFF00FF00u : J == 4 ? 0xF0F0F0F0u
+                         : J == 2 ? 0xCCCCCCCCu : 0xAAAAAAAAu;
+    const uint32_t other = lane_xor<J>(x);
+    const bool upper = (lane & J) != 0;
+    const uint32_t keep = upper ? M : ~M;               // bits this lane keeps
+    const uint32_t rot = __builtin_amdgcn_alignbit(other, other, upper ? J : 32 - J);   // >> J for the upper row, << J for the lower
+    return (x & keep) | (rot & ~keep);
+}
+
+// Lane c (of 32) holds the fixed-point value of column c; returns, in lane p, the packed word of plane p.
+__device__ __forceinline__ uint32_t bit_transpose32(uint32_t x, int lane)
+{
+    x = transpose_stage<16>(x, lane);
+    x = transpose_stage<8>(x, lane);
+    x = transpose_stage<4>(x, lane);
+    x = transpose_stage<2>(x, lane);
+    x = transpose_stage<1>(x, lane);
+    return x;
+}
+
+// Plane word -> the four A-operand registers (FP4 codes 2.0, 1.0, 0.5, 0.5 facing the weight codes 0.5, 1.0, 2.0, 2.0)
+__device__ __forceinline__ void expand_plane(uint32_t pw, u32x4 &dst)
+{
+    dst.x = (pw & 0x11111111u) << 2;
+    dst.y = pw & 0x22222222u;
+    dst.z = (pw & 0x44444444u) >> 2;
+    dst.w = (pw >> 3) & 0x11111111u;
+}
+
+__device__ __forceinline__ v8i as_operand(const u32x4 v)
+{
+    v8i r = {(int)v.x, (int)v.y, (int)v.z, (int)v.w, 0, 0, 0, 0};   // FP4 operands use the first four registers
+    return r;
+}
+
+__device__ __forceinline__ v8i weight_operand(uint32_t w)
+{
+    v8i r = {(int)(w & 0x11111111u), (int)(w & 0x22222222u), (int)(w & 0x44444444u),
+             (int)((w >> 1) & 0x44444444u), 0, 0, 0, 0};
+    return r;
+}
+
+__device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
+{
+    // cbsz = blgp = 4: both operands FP4 (E2M1); block scales 2^0 (E8M0 code 127)
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, 0x7F, 0, 0x7F);
+}
+
+template <int NQ>
+struct Cfg {
+    static constexpr int RU = NQ >= 4 ? 2 : 8 / NQ;   // units (row tile, bitlayer) whose blocks are in flight per wave
+};
+
+template <int NQ>
+__global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
+{
+    constexpr int RU = Cfg<NQ>::RU;
+    __shared__ int2 abuf[2][PB_MAX_BITS][kTileRows];   // (low 16 planes, high 16 planes) sums per bitlayer and row
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int n = blockIdx.y;
+    const int m = a.m;
+    const int q0 = wave * NQ;                                   // first chunk of this wave's column slice
+    const int nq = min(NQ, a.cq - q0);                          // chunks it really has (>= 1 by construction)
+    const int rt0 = blockIdx.x * a.rounds_per_wg;
+    const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
+    const int U = rounds * m;
+
+    // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
+    const size_t base_off = ((size_t)rt0 * a.cq + q0) * 1024;
+    const char *base = reinterpret_cast<const char *>(a.packed) + base_off;
+    const uint32_t avail = (uint32_t)(a.packed_bytes - base_off);
+    const uint32_t round_bytes = (uint32_t)a.cq * 1024;
+    const int voff = lane * 16;
+    u32x4 ring[RU][NQ];
+    uint32_t ld_soff = 0;
+    int ld_i = 0, ld_u = 0;
+    auto issue = [&](u32x4 (&dst)[NQ]) {
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, ld_u < U ? (int)avail : 0, 0x00020000);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            if (q < nq) dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)ld_soff, /*nt*/ 2);
+            else dst[q] = u32x4{0, 0, 0, 0};
+        }
+        __builtin_amdgcn_sched_barrier(0x7);
+        ++ld_u;
+        if (++ld_i == m) { ld_i = 0; ld_soff += round_bytes - (uint32_t)(m - 1) * a.layer_bytes; }
+        else ld_soff += a.layer_bytes;
+    };
+#pragma unroll
+    for (int k = 0; k < RU; ++k) issue(ring[k]);
+
+    // ---- the planes of this wave's slice, expanded to A operands, kept in registers ----
+    // lane l = 16 * kb + p: planes p (lo) and 16 + p (hi) of the words 16 * q + 4 * kb + t
+    const int kb = lane >> 4;
+    u32x4 pa_lo[NQ][4], pa_hi[NQ][4];
+    if (a.planes) {
+        const uint32_t *pl = a.planes + ((size_t)n * 32 + (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+            if (q < nq) {
+                lo = *reinterpret_cast<const uint4 *>(pl + q * 16);
+                hi = *reinterpret_cast<const uint4 *>(pl + (size_t)16 * a.cwp + q * 16);
+            }
+            expand_plane(lo.x, pa_lo[q][0]); expand_plane(lo.y, pa_lo[q][1]);
+            expand_plane(lo.z, pa_lo[q][2]); expand_plane(lo.w, pa_lo[q][3]);
+            expand_plane(hi.x, pa_hi[q][0]); expand_plane(hi.y, pa_hi[q][1]);
+            expand_plane(hi.z, pa_hi[q][2]); expand_plane(hi.w, pa_hi[q][3]);
+        }
+    } else {
+        // Algorithm 2: x_q = Int(x * 2^f); then the bitwise transpose, 32 columns x 32 bits at a time in each
+        // half of the wave: lane (half H, column c) converts column c of word 16 q + 4 (2 H + e) + t.
+        const int C = a.cols0 + a.cols1;
+        const float *x0 = a.X0 + (size_t)n * a.cols0;
+        const float *x1 = a.X1 ? a.X1 + (size_t)n * a.cols1 : nullptr;
+        const int H = lane >> 5, c = lane & 31;
+        const bool odd = (kb & 1) != 0;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            float xv[4][2];
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int e = 0; e < 2; ++e) {
+                    const int col = 32 * (16 * (q0 + q) + 4 * (2 * H + e) + t) + c;
+                    float v = 0.0f;
+                    if (col < a.cols0) v = x0[col];
+                    else if (col < C) v = x1[col - a.cols0];
+                    xv[t][e] = v;
+                }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const uint32_t X =
+                    bit_transpose32((uint32_t)to_fixed_point(xv[t][0] * a.fscale, a.lim, a.lim_below, a.imax), lane);
+                const uint32_t Y =
+                    bit_transpose32((uint32_t)to_fixed_point(xv[t][1] * a.fscale, a.lim, a.lim_below, a.imax), lane);
+                // X: lane (H, p) has plane p of word (e = 0), Y: of word (e = 1).  Even kb keeps X's low plane and
+                // needs X's high plane from lane + 16; odd kb keeps Y's high plane and needs Y's low one from lane - 16.
+                const uint32_t recv = lane_xor<16>(odd ? X : Y);
+                expand_plane(odd ? recv : X, pa_lo[q][t]);
+                expand_plane(odd ? Y : recv, pa_hi[q][t]);
+            }
+        }
+    }
+
+    // per-lane plane weights: registers v of the low / high instruction hold planes 4 kb + v / 16 + 4 kb + v
+    float kl[4], kh[4];
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+        kl[v] = (float)(1 << (4 * kb + v));
+        kh[v] = (kb == 3 && v == 3) ? -kl[v] : kl[v];    // plane 31 weighs -2^31 (Algorithm 2)
+    }
+
+    // LDS sums start at zero
+    for (int i = threadIdx.x; i < 2 * PB_MAX_BITS * kTileRows; i += blockDim.x) (&abuf[0][0][0])[i] = make_int2(0, 0);
+    __syncthreads();
+
+    const float scv = a.scales ? a.scales[lane < m ? lane : m - 1] : 0.0f;   // lane i holds scales[i]
+    const int j = lane & 15;
+    int pi = 0, pr = 0;   // bitlayer and round of the unit being multiplied
+    for (int u0 = 0; u0 < U; u0 += RU) {
+#pragma unroll
+        for (int k = 0; k < RU; ++k) {
+            if (u0 + k < U) {
+                v4f acc_lo = {0.f, 0.f, 0.f, 0.f}, acc_hi = acc_lo;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    if (q < nq) {
+                        const u32x4 w = ring[k][q];
+                        v8i b;
+                        b = weight_operand(w.x);
+                        acc_lo = mfma_fp4(as_operand(pa_lo[q][0]), b, acc_lo);
+                        acc_hi = mfma_fp4(as_operand(pa_hi[q][0]), b, acc_hi);
+                        b = weight_operand(w.y);
+                        acc_lo = mfma_fp4(as_operand(pa_lo[q][1]), b, acc_lo);
+                        acc_hi = mfma_fp4(as_operand(pa_hi[q][1]), b, acc_hi);
+                        b = weight_operand(w.z);
+                        acc_lo = mfma_fp4(as_operand(pa_lo[q][2]), b, acc_lo);
+                        acc_hi = mfma_fp4(as_operand(pa_hi[q][2]), b, acc_hi);
+                        b = weight_operand(w.w);
+                        acc_lo = mfma_fp4(as_operand(pa_lo[q][3]), b, acc_lo);
+                        acc_hi = mfma_fp4(as_operand(pa_hi[q][3]), b, acc_hi);
+                    }
+                }
+                // plane weighting inside the lane.  Counts are <= 2048 (a slice has at most 2048 columns), so
+                // c0 + 2 c1 + 4 c2 +- 8 c3 < 2^15 and its multiple by 2^(4 kb) is exact in fp32 and < 2^27.
+                const float lo_f = acc_lo[0] * kl[0] + acc_lo[1] * kl[1] + acc_lo[2] * kl[2] + acc_lo[3] * kl[3];
+                const float hi_f = acc_hi[0] * kh[0] + acc_hi[1] * kh[1] + acc_hi[2] * kh[2] + acc_hi[3] * kh[3];
+                int2 *dst = &abuf[pr & 1][pi][j];
+                atomicAdd(&dst->x, (int)lo_f);
+                atomicAdd(&dst->y, (int)hi_f);
+                if (++pi == m) {
+                    // the row tile is complete in every slice: one wave (taking turns) scales and stores it
+                    pi = 0;
+                    __syncthreads();
+                    if (wave == pr % nwaves && lane < kTileRows) {
+                        const int row = (rt0 + pr) * kTileRows + lane;
+                        int2 *src = &abuf[pr & 1][0][lane];
+                        double z = 0.0;
+                        for (int i = 0; i < m; ++i) {
+                            const int2 v = src[i * kTileRows];
+                            src[i * kTileRows] = make_int2(0, 0);
+                            // A_i = lo + hi * 2^16 exactly: lo < 2^31 (unsigned), |hi| <= 2^30
+                            if (a.A) {
+                                if (row < a.R)
+                                    a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
+                                        (long long)(uint32_t)v.x + ((long long)v.y << 16);
+                            } else {
+                                const float si =
+                                    __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(scv), i));
+                                z += (double)si * ((double)(uint32_t)v.x + (double)v.y * 65536.0);
+                            }
+                        }
+                        if (!a.A && row < a.R) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
+                    }
+                    ++pr;
+                }
+            }
+            issue(ring[k]);
+        }
+    }
+}
+
+static int pick_nq(const Layout &L)
+{
+    // smallest slice (most waves per row, shortest transpose per wave) whose slice count fits a workgroup
+    if (const char *e = getenv("PB_TUNE_NQ")) {
+        int v = atoi(e);
+        if ((v == 1 || v == 2 || v == 4) && (L.cq + v - 1) / v <= (v == 1 ? 16 : 8)) return v;
+    }
+    return L.cq <= 16 ? 1 : 4;
+}
+
+int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
+                int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
+                int batch, float *Y, long long *A, hipStream_t st)
+{
+    MfmaArgs a;
+    a.packed = packed; a.X0 = X0; a.X1 = X1; a.planes = planes; a.scales = scales; a.Y = Y; a.A = A;
+    a.packed_bytes = packed_bytes(L);
+    a.layer_bytes = (uint32_t)(L.layer_words * 4);
+    a.cols0 = cols0; a.cols1 = cols1;
+    a.R = L.rows; a.rt_count = L.rt_count; a.cq = L.cq; a.cwp = L.cwp;
+    a.m = bits_used;
+    a.batch = batch;
+    a.fscale = ldexpf(1.0f, frac_bits);
+    a.lim = ldexpf(1.0f, act_bits - 1);
+    a.lim_below = nextafterf(a.lim, 0.0f);
+    a.imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
+    a.out_scale = ldexp(1.0, -frac_bits);
+    const int nq = pick_nq(L);
+    const int S = (L.cq + nq - 1) / nq;
+    if (S > (nq == 1 ? 16 : 8)) return (int)hipErrorInvalidValue;
+    // workgroups: enough waves to fill the chip (16 per CU), each with whole row tiles
+    int target_waves = 4096;
+    if (const char *e = getenv("PB_TUNE_WAVES")) target_waves = atoi(e);
+    int wgs = target_waves / S;
+    if (wgs < 1) wgs = 1;
+    if (wgs > L.rt_count) wgs = L.rt_count;
+    a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
+    wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
+    const dim3 grid((unsigned)wgs, (unsigned)batch), block((unsigned)S * 64);
+    switch (nq) {
+        case 1: hipLaunchKernelGGL(k_mfma<1>, grid, block, 0, st, a); break;
+        case 2: hipLaunchKernelGGL(k_mfma<2>, grid, block, 0, st, a); break;
+        default: hipLaunchKernelGGL(k_mfma<4>, grid, block, 0, st, a); break;
+    }
+    return (int)hipGetLastError();
+}
+
+}  // namespace pb

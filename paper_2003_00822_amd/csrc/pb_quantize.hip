@@ -54,8 +54,8 @@ __device__ __forceinline__ int quantize_code(float w, float d, int bits)
 }
 
 // one thread per (padded row, padded word): builds that word of every bitlayer
-__global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, int rows, int cols, int bits, int cw,
-                                              int cwp, int rows_p, size_t layer_words,
+__global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint32_t layout, int rows, int cols,
+                                              int bits, int cw, int cwp, int rows_p, size_t layer_words,
                                               const uint32_t *__restrict__ absmax_slot, uint32_t *__restrict__ packed)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -78,9 +78,10 @@ __global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, int r
                 if (i < bits) wd[i] |= ((u >> (bits - 1 - i)) & 1u) << b;
         }
     }
+    const size_t pos = word_index(layout, cwp, r, w);
 #pragma unroll
     for (int i = 0; i < PB_MAX_BITS; ++i)
-        if (i < bits) packed[(size_t)i * layer_words + idx] = wd[i];
+        if (i < bits) packed[(size_t)i * layer_words + pos] = wd[i];
 }
 
 // reads max|W| from scales[0] (where k_absmax left it) and writes the layer scales
@@ -94,16 +95,17 @@ __global__ void k_scales(float *scales, int bits)
     }
 }
 
-__global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ packed, int rows, int cols, int bits,
-                                                int cwp, size_t layer_words, int32_t *__restrict__ q)
+__global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ packed, uint32_t layout, int rows, int cols,
+                                                int bits, int cwp, size_t layer_words, int32_t *__restrict__ q)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)rows * (size_t)cols) return;
     int r = (int)(idx / (size_t)cols);
     int c = (int)(idx % (size_t)cols);
     uint32_t u = 0;
+    const size_t pos = word_index(layout, cwp, r, c >> 5);
     for (int i = 0; i < bits; ++i) {
-        uint32_t word = packed[(size_t)i * layer_words + (size_t)r * cwp + (c >> 5)];
+        uint32_t word = packed[(size_t)i * layer_words + pos];
         u |= ((word >> (c & 31)) & 1u) << (bits - 1 - i);
     }
     int32_t v = (int32_t)(u << (32 - bits)) >> (32 - bits);  // sign-extend the B-bit code
@@ -120,8 +122,8 @@ int launch_quantize_pack(const float *W, const Layout &L, uint32_t *packed, floa
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(k_absmax, dim3(blocks), dim3(256), 0, st, W, n, slot);
     size_t total = L.layer_words;
-    hipLaunchKernelGGL(k_pack, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, L.rows, L.cols, L.bits,
-                       L.cw, L.cwp, L.rows_p, L.layer_words, slot, packed);
+    hipLaunchKernelGGL(k_pack, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, L.layout, L.rows, L.cols,
+                       L.bits, L.cw, L.cwp, L.rows_p, L.layer_words, slot, packed);
     hipLaunchKernelGGL(k_scales, dim3(1), dim3(64), 0, st, scales, L.bits);
     return (int)hipGetLastError();
 }
@@ -129,8 +131,8 @@ int launch_quantize_pack(const float *W, const Layout &L, uint32_t *packed, floa
 int launch_unpack(const uint32_t *packed, const Layout &L, int32_t *q, hipStream_t st)
 {
     size_t n = (size_t)L.rows * (size_t)L.cols;
-    hipLaunchKernelGGL(k_unpack, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, L.rows, L.cols, L.bits,
-                       L.cwp, L.layer_words, q);
+    hipLaunchKernelGGL(k_unpack, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, L.layout, L.rows, L.cols,
+                       L.bits, L.cwp, L.layer_words, q);
     return (int)hipGetLastError();
 }
 

@@ -18,9 +18,11 @@ PB_OK, PB_EINVAL, PB_EALIGN, PB_ESIZE, PB_EHIP = 0, -1, -2, -3, -4
 PB_MAX_BITS = 16
 PB_MAX_COLS = 32768
 PB_MAX_BATCH = 4096
+PB_LAYOUT_ROWMAJOR_V1 = 0x50420001   # AND + popcount kernel
+PB_LAYOUT_TILE16_V1 = 0x50420002     # matrix-core kernel (the default up to 16384 columns)
 
 EXPORTS = [
-    "pb_desc_init", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
+    "pb_desc_init", "pb_desc_init_layout", "pb_quantize_pack_desc", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
     "pb_matmul_acc", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
 ]
 
@@ -53,6 +55,10 @@ def lib():
         L = ctypes.CDLL(LIB_PATH)
         L.pb_desc_init.argtypes = [_D, _I, _I, _I]
         L.pb_desc_init.restype = _I
+        L.pb_desc_init_layout.argtypes = [_D, _I, _I, _I, ctypes.c_uint32]
+        L.pb_desc_init_layout.restype = _I
+        L.pb_quantize_pack_desc.argtypes = [_P, _D, _P, _P, _P]
+        L.pb_quantize_pack_desc.restype = _I
         L.pb_packed_bytes.argtypes = [_D]
         L.pb_packed_bytes.restype = ctypes.c_size_t
         L.pb_workspace_bytes.argtypes = [_D, _I]
@@ -118,6 +124,15 @@ def pb_desc_init(rows: int, cols: int, bits: int, frac_bits: int = 16, act_bits:
     return d
 
 
+def pb_desc_init_layout(rows: int, cols: int, bits: int, layout: int, frac_bits: int = 16,
+                        act_bits: int = 32) -> pb_desc:
+    d = pb_desc()
+    _check(lib().pb_desc_init_layout(ctypes.byref(d), rows, cols, bits, layout), "pb_desc_init_layout")
+    d.frac_bits = frac_bits
+    d.act_bits = act_bits
+    return d
+
+
 def pb_packed_bytes(d: pb_desc) -> int:
     return int(lib().pb_packed_bytes(ctypes.byref(d)))
 
@@ -137,6 +152,12 @@ def alloc_workspace(d: pb_desc, batch: int, device="cuda") -> torch.Tensor:
 def pb_quantize_pack(W, rows, cols, bits, packed, scales, stream=None):
     _check(lib().pb_quantize_pack(_ptr(W, torch.float32, "W"), rows, cols, bits, _ptr(packed, torch.uint8, "packed"),
                                   _ptr(scales, torch.float32, "scales"), _stream(stream)), "pb_quantize_pack")
+
+
+def pb_quantize_pack_desc(W, d, packed, scales, stream=None):
+    _check(lib().pb_quantize_pack_desc(_ptr(W, torch.float32, "W"), ctypes.byref(d),
+                                       _ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float32, "scales"),
+                                       _stream(stream)), "pb_quantize_pack_desc")
 
 
 def pb_unpack(packed, d, q, stream=None):
@@ -187,17 +208,21 @@ def pb_lstm_cell(packed, scales, d, bits_used, x_t, input_size, h_prev, c_prev, 
 class PackedLinear:
     """Convenience holder: one quantized, packed weight matrix with its scales and a workspace."""
 
-    def __init__(self, W: torch.Tensor, bits: int, max_batch: int = 1, frac_bits: int = 16, act_bits: int = 32):
+    def __init__(self, W: torch.Tensor, bits: int, max_batch: int = 1, frac_bits: int = 16, act_bits: int = 32,
+                 layout: int | None = None):
         assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2
         W = W.contiguous()
         self.rows, self.cols = W.shape
         self.bits = bits
-        self.desc = pb_desc_init(self.rows, self.cols, bits, frac_bits, act_bits)
+        if layout is None:
+            self.desc = pb_desc_init(self.rows, self.cols, bits, frac_bits, act_bits)
+        else:
+            self.desc = pb_desc_init_layout(self.rows, self.cols, bits, layout, frac_bits, act_bits)
         self.packed = alloc_packed(self.desc, W.device)
         self.scales = torch.empty(max(bits, 4), dtype=torch.float32, device=W.device)
         self.max_batch = max_batch
         self.workspace = alloc_workspace(self.desc, max_batch, W.device)
-        pb_quantize_pack(W, self.rows, self.cols, bits, self.packed, self.scales)
+        pb_quantize_pack_desc(W, self.desc, self.packed, self.scales)
 
     def __call__(self, X: torch.Tensor, bits_used: int | None = None, out: torch.Tensor | None = None):
         X = X.reshape(-1, self.cols)

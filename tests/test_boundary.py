@@ -41,12 +41,26 @@ def test_header_symbols_exported(pb):
 def test_desc_and_sizes(pb):
     d = pb.pb_desc_init(4096, 4096, 8)
     assert (d.rows, d.cols, d.bits, d.frac_bits, d.act_bits) == (4096, 4096, 8, 16, 32)
+    assert d.layout == pb.PB_LAYOUT_TILE16_V1
     assert pb.pb_packed_bytes(d) == 8 * 4096 * 4096 // 8
-    # ragged: 100 x 3000 -> rows padded to 100, words per row padded to 96
+    # tiled layout, ragged: rows padded to 16, words per row to 16
     d = pb.pb_desc_init(100, 3000, 3)
-    assert pb.pb_packed_bytes(d) == 3 * 100 * 96 * 4
+    assert pb.pb_packed_bytes(d) == 3 * 112 * 96 * 4
     d = pb.pb_desc_init(10, 784, 2)
+    assert pb.pb_packed_bytes(d) == 2 * 16 * 32 * 4
+    # row-major layout, ragged: 100 x 3000 -> rows padded to 100, words per row padded to 96
+    d = pb.pb_desc_init_layout(100, 3000, 3, pb.PB_LAYOUT_ROWMAJOR_V1)
+    assert pb.pb_packed_bytes(d) == 3 * 100 * 96 * 4
+    d = pb.pb_desc_init_layout(10, 784, 2, pb.PB_LAYOUT_ROWMAJOR_V1)
     assert pb.pb_packed_bytes(d) == 2 * 12 * 32 * 4
+    # the tiled layout stops at 16384 columns; wider matrices get the row-major one
+    assert pb.pb_desc_init(8, 16385, 2).layout == pb.PB_LAYOUT_ROWMAJOR_V1
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_desc_init_layout(8, 16385, 2, pb.PB_LAYOUT_TILE16_V1)
+    assert e.value.status == pb.PB_ESIZE
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_desc_init_layout(8, 64, 2, 7)
+    assert e.value.status == pb.PB_EINVAL
     ws1 = pb.pb_workspace_bytes(d, 1)
     ws4 = pb.pb_workspace_bytes(d, 4)
     assert ws1 >= 32 * 32 * 4 + 10 * 4 and ws4 > ws1

@@ -20,14 +20,24 @@ def pb():
     return pbmod
 
 
+# every case runs on both packed layouts: the matrix-core kernel (default) and the AND + popcount kernel
+LAYOUTS = {"mfma": 0x50420002, "popc": 0x50420001}
+
+
+@pytest.fixture(params=sorted(LAYOUTS), scope="module")
+def layout(request):
+    return LAYOUTS[request.param]
+
+
 def dev(a):
     return torch.from_numpy(np.ascontiguousarray(a)).cuda()
 
 
-def run_layer(pb, W, bits, X, m_list, frac_bits=16, act_bits=32, check_y=True):
+def run_layer(pb, W, bits, X, m_list, frac_bits=16, act_bits=32, check_y=True, layout=None):
     R, C = W.shape
     N = X.shape[0]
-    lin = pb.PackedLinear(dev(W), bits, max_batch=N, frac_bits=frac_bits, act_bits=act_bits)
+    lin = pb.PackedLinear(dev(W), bits, max_batch=N, frac_bits=frac_bits, act_bits=act_bits, layout=layout)
+    assert layout is None or lin.desc.layout == layout
     prep = po.prepare(W, bits)
     # Algorithm 1: codes and scales
     q_gpu = lin.unpack().cpu().numpy()
@@ -55,26 +65,26 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("shape", SHAPES)
-def test_shapes_all_layers(pb, shape):
+def test_shapes_all_layers(pb, layout, shape):
     R, C = shape
     bits = 1 + (R + C) % 8
     W, X = synth.ragged(R, C, batch=1, case=1)
     print("shape", shape, "bits", bits, flush=True)
-    run_layer(pb, W, bits, X, sorted({1, bits, max(1, bits // 2)}))
+    run_layer(pb, W, bits, X, sorted({1, bits, max(1, bits // 2)}), layout=layout)
 
 
 @pytest.mark.parametrize("bits", [1, 2, 3, 4, 5, 6, 7, 8, 12, 16])
-def test_every_bit_width_and_prefix(pb, bits):
+def test_every_bit_width_and_prefix(pb, layout, bits):
     W, X = synth.ragged(70, 200, batch=1, case=bits, xdist="uniform")
     print("bits", bits, flush=True)
-    run_layer(pb, W, bits, X, list(range(1, bits + 1)))
+    run_layer(pb, W, bits, X, list(range(1, bits + 1)), layout=layout)
 
 
 @pytest.mark.parametrize("xdist", ["normal", "uniform", "relu", "wide"])
-def test_activation_distributions(pb, xdist):
+def test_activation_distributions(pb, layout, xdist):
     W, X = synth.ragged(96, 1000, batch=3, case=3, xdist=xdist)
     print("xdist", xdist, flush=True)
-    run_layer(pb, W, 4, X, [1, 4])
+    run_layer(pb, W, 4, X, [1, 4], layout=layout)
 
 
 def test_fixed_point_conversion(pb):
@@ -94,7 +104,7 @@ def test_fixed_point_conversion(pb):
         assert (xq.cpu().numpy() == want).all(), (f, k)
 
 
-def test_special_activation_vectors(pb):
+def test_special_activation_vectors(pb, layout):
     R, C, bits = 37, 200, 5
     W, _ = synth.ragged(R, C, case=2)
     cases = {
@@ -109,23 +119,38 @@ def test_special_activation_vectors(pb):
     cases["onehot"] = onehot
     for name, X in cases.items():
         print("special", name, flush=True)
-        run_layer(pb, W, bits, X, [1, 3, 5])
+        run_layer(pb, W, bits, X, [1, 3, 5], layout=layout)
 
 
-def test_reduced_activation_precision(pb):
+def test_reduced_activation_precision(pb, layout):
     # Section 3.1: k (activation precision) of 8 or 16 planes; the fixed point moves with it
     W, X = synth.ragged(50, 300, batch=2, case=5, xdist="uniform")
     for (f, k) in [(6, 8), (14, 16), (20, 32)]:
         print("act", f, k, flush=True)
-        run_layer(pb, W, 4, X, [2, 4], frac_bits=f, act_bits=k)
+        run_layer(pb, W, 4, X, [2, 4], frac_bits=f, act_bits=k, layout=layout)
 
 
-def test_config1_fc_1024_definition_level(pb):
+def test_prepared_halves_equal_whole_call(pb, layout):
+    """pb_act_prep + pb_matmul_prepared (planes through memory) against pb_matmul and the oracle."""
+    W, X = synth.ragged(150, 2100, batch=2, case=7, xdist="normal")
+    bits, m = 6, 5
+    lin = pb.PackedLinear(dev(W), bits, max_batch=2, layout=layout)
+    ref = oracle_reference(W, bits, X, m)
+    Xd = dev(X)
+    Y1 = lin(Xd, m).cpu().numpy()
+    Y2 = torch.empty((2, 150), dtype=torch.float32, device="cuda")
+    pb.pb_act_prep(lin.desc, Xd, 2, lin.workspace)
+    pb.pb_matmul_prepared(lin.packed, lin.scales, lin.desc, m, 2, Y2, lin.workspace)
+    assert_y_close(Y1, ref["Y"], ref["A"], ref["scales"])
+    assert (Y2.cpu().numpy().view(np.int32) == Y1.view(np.int32)).all()
+
+
+def test_config1_fc_1024_definition_level(pb, layout):
     """Config 1, checked against the byte-per-bit tier of the oracle (Algorithm 2 taken literally)."""
     W, X = synth.fc_small()
     bits = 4
     prep = po.prepare(W, bits)
-    lin = pb.PackedLinear(dev(W), bits)
+    lin = pb.PackedLinear(dev(W), bits, layout=layout)
     for m in range(1, bits + 1):
         A, T, Y = po.matmul_bitserial(prep["layers"], prep["scales"], prep["s"], m, X)
         A_gpu = lin.acc(dev(X), m).cpu().numpy()
@@ -135,13 +160,13 @@ def test_config1_fc_1024_definition_level(pb):
 
 
 @pytest.mark.parametrize("bits", [8, 3])
-def test_config2_fc_4096_full_size(pb, bits):
+def test_config2_fc_4096_full_size(pb, layout, bits):
     W, X = synth.fc_square(4096, 0.02)
     print("cfg2 bits", bits, flush=True)
-    run_layer(pb, W, bits, X, list(range(1, bits + 1)))
+    run_layer(pb, W, bits, X, list(range(1, bits + 1)), layout=layout)
 
 
-def test_config3_mlp_layers(pb):
+def test_config3_mlp_layers(pb, layout):
     """Config 3: each layer fed with the oracle's previous-layer output (ReLU), so integers must match."""
     Ws, X = synth.mlp()
     bits = 6
@@ -149,23 +174,23 @@ def test_config3_mlp_layers(pb):
     for li, W in enumerate(Ws):
         print("mlp layer", li, W.shape, flush=True)
         m = [bits, 2, 4][li]
-        run_layer(pb, W, bits, x, [m])
+        run_layer(pb, W, bits, x, [m], layout=layout)
         ref = oracle_reference(W, bits, x, m)
         x = np.maximum(ref["Y"], 0.0).astype(np.float32)
 
 
-def test_config5_large_fc_batch(pb):
+def test_config5_large_fc_batch(pb, layout):
     W, X = synth.fc_large(batch=4)
     print("cfg5 8192 batch 4", flush=True)
-    run_layer(pb, W, 2, X, [2])
+    run_layer(pb, W, 2, X, [2], layout=layout)
     W16, X16 = synth.ragged(64, 8192, batch=16, case=9)
-    run_layer(pb, W16, 8, X16, [8])
+    run_layer(pb, W16, 8, X16, [8], layout=layout)
 
 
-def test_extra_16384(pb):
+def test_extra_16384(pb, layout):
     W, X = synth.fc_square(16384, 0.01, cfg=6)
     bits = 2
-    lin = pb.PackedLinear(dev(W), bits)
+    lin = pb.PackedLinear(dev(W), bits, layout=layout)
     # oracle on sampled rows only (full size in the launch configuration of the benchmark)
     rng = np.random.default_rng(0)
     rows = sorted(rng.choice(16384, size=48, replace=False).tolist() + [0, 16383])
@@ -180,7 +205,7 @@ def test_extra_16384(pb):
         assert_y_close(Y_gpu[:, r], y, sub[:, 0, :], prep["scales"])
 
 
-def test_lstm_cell_config4(pb):
+def test_lstm_cell_config4(pb, layout):
     """Config 4: 35 sequential LSTM steps.  Integer parity is checked per step with oracle-fed state
     (teacher forcing); the free-running GPU recurrence is compared to a tolerance."""
     H = I = 1500
@@ -188,7 +213,7 @@ def test_lstm_cell_config4(pb):
     bits, m = 4, 4
     prep = po.prepare(W, bits)
     lw = po.pack_words(prep["layers"])
-    lin = pb.PackedLinear(dev(W), bits)
+    lin = pb.PackedLinear(dev(W), bits, layout=layout)
     d, packed, scales, ws = lin.desc, lin.packed, lin.scales, lin.workspace
     bias_d = dev(bias)
     h_or = np.zeros((1, H), dtype=np.float32)
