@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the PrecisionBatching hot path on one MI355X.
 
-A step is one pass of the whole path (activation conversion + bit transpose, AND/popcount
-product, plane and bitlayer accumulation) over one batch-1 activation vector for every
+A step is one pass of the whole path (activation conversion + bit transpose, 1-bit products,
+plane and bitlayer accumulation) over one batch-1 activation vector for every
 bits_used = 1..B of one FC layer (default: 4096 x 4096, B = 8): B calls of pb_matmul.
+--layout mfma (default) runs the matrix-core kernel (one launch per call), --layout popc the
+AND + popcount kernel (activation kernel + product kernel per call).
 Weights are resident in HBM before the timed region; each call reads a different copy out of
 a pool larger than the last-level cache, so the weight stream really comes from HBM ("cold").
 
@@ -25,6 +27,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0                       # MI355X HBM3E, published
 ALU_PEAK_GOPS = 256 * 4 * 16 * 2.4          # CUs x SIMDs x lanes x GHz = 39321.6 G int32 lane-ops/s
+FP4_PEAK_TFLOPS = 10100.0                   # dense FP4 matrix-core peak, published
 LLC_BYTES = 256 << 20                       # last-level (Infinity) cache
 POOL_BYTES = 768 << 20                      # weight copies rotated through: 3x the last-level cache
 
@@ -36,6 +39,8 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--size", type=int, default=4096, help="FC layer is size x size (4096 = the headline config)")
     ap.add_argument("--bits", type=int, default=8, help="stored bitlayers B; bits_used sweeps 1..B")
+    ap.add_argument("--layout", choices=["mfma", "popc"], default="mfma",
+                    help="packed layout = kernel: matrix cores (default) or AND + popcount")
     ap.add_argument("--warm", action="store_true", help="reuse one weight copy (cache-resident) instead of the pool")
     ap.add_argument("--eager", action="store_true", help="plain launches from Python instead of HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -63,10 +68,11 @@ def main():
     W, X = synth.fc_square(n, std, batch=1, cfg=2 if n == 4096 else 5)
     Wd = torch.from_numpy(W).to(dev)
     Xd = torch.from_numpy(X).to(dev)
-    d = pb.pb_desc_init(n, n, B)
+    mfma = args.layout == "mfma"
+    d = pb.pb_desc_init_layout(n, n, B, pb.PB_LAYOUT_TILE16_V1 if mfma else pb.PB_LAYOUT_ROWMAJOR_V1)
     packed = pb.alloc_packed(d, dev)
     scales = torch.empty(max(B, 4), dtype=torch.float32, device=dev)
-    pb.pb_quantize_pack(Wd, n, n, B, packed, scales)
+    pb.pb_quantize_pack_desc(Wd, d, packed, scales)
     torch.cuda.synchronize()
     del Wd
     pbytes = packed.numel()
@@ -120,9 +126,10 @@ def main():
     step_bytes = layer_bytes * B * (B + 1) // 2
     value = step_bytes / sec_per_step / 1e9
 
-    # plane statistics of this input (written by the activation kernel): planes actually multiplied
+    # plane statistics of this input (written by the activation kernel): planes the popcount kernel multiplies
+    pb.pb_act_prep(d, Xd, 1, ws)
     meta = ws[:64].view(torch.int32).cpu().numpy()
-    nplanes = int(meta[3])
+    nplanes = int(meta[3]) if not mfma else 32
 
     # ---- per bits_used: whole call (prep + product) and the product kernel alone ----
     per_m = []
@@ -141,14 +148,13 @@ def main():
                 pb.pb_matmul_prepared(pool[i], scales, d, m, 1, Y, ws)
         return f
 
-    pb.pb_act_prep(d, Xd, 1, ws)
     for m in range(1, B + 1):
         t_call = timed(capture(call_loop(m)), reps) / copies
-        t_kern = timed(capture(kern_loop(m)), reps) / copies
+        # matrix-core layout: the call IS one kernel; popcount layout: the product kernel without the activation kernel
+        t_kern = t_call if mfma else timed(capture(kern_loop(m)), reps) / copies
         kern_time_sum += t_kern
         wbytes = layer_bytes * m
-        lane_ops = 2.0 * nplanes * (wbytes / 4)      # one AND + one popcount-accumulate per (word, plane)
-        per_m.append({
+        row = {
             "bits_used": m,
             "us_per_call": round(t_call * 1e6, 3),
             "matvecs_per_s": round(1.0 / t_call, 1),
@@ -156,26 +162,38 @@ def main():
             "kernel_us": round(t_kern * 1e6, 3),
             "kernel_GBps": round(wbytes / t_kern / 1e9, 1),
             "kernel_hbm_frac": round(wbytes / t_kern / 1e9 / HBM_PEAK_GBS, 4),
-            "kernel_alu_frac": round(lane_ops / t_kern / 1e9 / ALU_PEAK_GOPS, 4),
-        })
+        }
+        if mfma:   # 2 flops per (weight bit, plane): 32 planes
+            row["kernel_mfma_frac"] = round(2.0 * 32 * wbytes * 8 / t_kern / 1e12 / FP4_PEAK_TFLOPS, 4)
+        else:      # one AND + one popcount-accumulate per (word, plane)
+            row["kernel_alu_frac"] = round(2.0 * nplanes * (wbytes / 4) / t_kern / 1e9 / ALU_PEAK_GOPS, 4)
+        per_m.append(row)
 
-    def prep_loop():
-        for _ in range(copies):
-            pb.pb_act_prep(d, Xd, 1, ws)
-    t_prep = timed(capture(prep_loop), reps) / copies
+    t_prep = 0.0
+    if not mfma:
+        def prep_loop():
+            for _ in range(copies):
+                pb.pb_act_prep(d, Xd, 1, ws)
+        t_prep = timed(capture(prep_loop), reps) / copies
 
-    # ---- roofline of the dominant kernel (k_matvec) over the sweep bits_used = 1..B ----
+    # ---- roofline of the dominant kernel over the sweep bits_used = 1..B (average launch) ----
     avg_kernel_s = kern_time_sum / B
     avg_bytes = step_bytes / B
-    avg_lane_ops = 2.0 * nplanes * (avg_bytes / 4)
     hbm_frac = avg_bytes / avg_kernel_s / 1e9 / HBM_PEAK_GBS
-    alu_frac = avg_lane_ops / avg_kernel_s / 1e9 / ALU_PEAK_GOPS
     roof_hbm = {"bound": "hbm", "achieved": round(avg_bytes / avg_kernel_s / 1e9, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(hbm_frac, 4), "traffic": None}
-    roof_alu = {"bound": "alu", "achieved": round(avg_lane_ops / avg_kernel_s / 1e9, 1),
-                "peak": round(ALU_PEAK_GOPS, 1), "unit": "Gop/s", "frac": round(alu_frac, 4), "traffic": None}
-    binding, other = (roof_alu, roof_hbm) if alu_frac > hbm_frac else (roof_hbm, roof_alu)
-    binding["kernel"] = other["kernel"] = "k_matvec"
+    if mfma:
+        tflops = 2.0 * 32 * avg_bytes * 8 / avg_kernel_s / 1e12
+        cmp_frac = tflops / FP4_PEAK_TFLOPS
+        roof_cmp = {"bound": "mfma", "achieved": round(tflops, 1), "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(cmp_frac, 4), "traffic": None}
+    else:
+        avg_lane_ops = 2.0 * nplanes * (avg_bytes / 4)
+        cmp_frac = avg_lane_ops / avg_kernel_s / 1e9 / ALU_PEAK_GOPS
+        roof_cmp = {"bound": "alu", "achieved": round(avg_lane_ops / avg_kernel_s / 1e9, 1),
+                    "peak": round(ALU_PEAK_GOPS, 1), "unit": "Gop/s", "frac": round(cmp_frac, 4), "traffic": None}
+    binding, other = (roof_cmp, roof_hbm) if cmp_frac > hbm_frac else (roof_hbm, roof_cmp)
+    binding["kernel"] = other["kernel"] = "k_mfma" if mfma else "k_matvec"
     binding["avg_launch_us"] = other["avg_launch_us"] = round(avg_kernel_s * 1e6, 3)
     binding["active_planes"] = nplanes
 
@@ -190,12 +208,15 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 popcount / int64 accumulate",
+        "dtype": "fp4 0/1 operands, fp32 exact counts, int64 accumulate" if mfma
+                 else "u32 popcount / int64 accumulate",
         "data": "synthetic",
         "config": {"workload": "FC %dx%d, weight bitlayers B=%d, bits_used swept 1..%d (one call each per step), "
                                "batch 1, x~N(0,1) as 32-bit fixed point" % (n, n, B, B),
                    "weights": "cold: %d copies (%d MiB) rotated" % (copies, copies * pbytes >> 20) if not args.warm
                    else "warm: one copy, cache resident",
+                   "kernel": "matrix cores (FP4 MFMA on 0/1 planes), one launch per call" if mfma
+                   else "AND + popcount, activation kernel + product kernel per call",
                    "launch": "eager" if args.eager else "hip graph replay (%d steps per graph)" % G,
                    "active_planes": nplanes},
         "matvecs_per_s": round(B / sec_per_step, 1),

@@ -57,49 +57,72 @@ struct MfmaArgs {
     int m;                      // bitlayers to accumulate
     int batch;
     int rounds_per_wg;          // row tiles per workgroup
-    float fscale, lim, lim_below;
-    int imax;
+    float fscale;               // 2^frac_bits
+    int imin, imax;             // range of the act_bits-bit fixed-point values
     double out_scale;           // 2^-frac_bits
 };
 
-// k-bit saturating, toward-zero conversion of p = x * 2^f; NaN -> 0 (same rule as the stand-alone activation kernel)
-__device__ __forceinline__ int32_t to_fixed_point(float p, float lim, float lim_below, int32_t imax)
+// x_q = Int(x * 2^f) as a k-bit two's-complement value: toward zero, saturating, NaN -> 0.  V_CVT_I32_F32 does
+// exactly that for k = 32 (out-of-range inputs saturate, NaN converts to 0); narrower k clamp the integer.
+__device__ __forceinline__ int32_t to_fixed_point(float x, float fscale, int32_t imin, int32_t imax)
 {
-    const float pc = fminf(fmaxf(p, -lim), lim_below);
-    int32_t r = (int32_t)pc;
-    r = (p >= lim) ? imax : r;
-    return (p != p) ? 0 : r;
+    int32_t r;
+    const float p = x * fscale;   // exact: a power of two
+    asm("v_cvt_i32_f32 %0, %1" : "=v"(r) : "v"(p));
+    return min(max(r, imin), imax);
+}
+
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_mov_dpp((int)v, CTRL, 0xf, 0xf, true);
+}
+
+// value of lane (l ^ J) for J < 16, inside each row of 16 lanes, on the vector ALU alone (DPP modifiers)
+template <int J>
+__device__ __forceinline__ uint32_t row_xor(uint32_t v)
+{
+    if constexpr (J == 8) return dpp_mov<0x128>(v);                     // row_ror:8
+    else if constexpr (J == 4) return dpp_mov<0x1B>(dpp_mov<0x141>(v)); // row_half_mirror (l ^ 7), then quad_perm [3,2,1,0] (l ^ 3)
+    else if constexpr (J == 2) return dpp_mov<0x4E>(v);                 // quad_perm [2,3,0,1]
+    else return dpp_mov<0xB1>(v);                                       // quad_perm [1,0,3,2]
+}
+
+// Per-lane constants of the 16 x 16 bit-matrix transpose across a row of 16 lanes (both 16-bit halves of a
+// register at once): in stage J lanes l and l ^ J exchange the bit positions that have bit J set (lower lane)
+// / clear (upper lane); keep = the positions a lane keeps, rot = right-rotation that moves the partner's bits
+// into the others (>> J for the upper lane, << J for the lower).
+struct TransposeConsts {
+    uint32_t keep8, keep4, keep2, keep1;
+    uint32_t rot8, rot4, rot2, rot1;
+};
+
+__device__ __forceinline__ TransposeConsts transpose_consts(int lane)
+{
+    TransposeConsts c;
+    c.keep8 = (lane & 8) ? 0xFF00FF00u : 0x00FF00FFu; c.rot8 = (lane & 8) ? 8 : 24;
+    c.keep4 = (lane & 4) ? 0xF0F0F0F0u : 0x0F0F0F0Fu; c.rot4 = (lane & 4) ? 4 : 28;
+    c.keep2 = (lane & 2) ? 0xCCCCCCCCu : 0x33333333u; c.rot2 = (lane & 2) ? 2 : 30;
+    c.keep1 = (lane & 1) ? 0xAAAAAAAAu : 0x55555555u; c.rot1 = (lane & 1) ? 1 : 31;
+    return c;
 }
 
 template <int J>
-__device__ __forceinline__ uint32_t lane_xor(uint32_t v)
+__device__ __forceinline__ uint32_t transpose_stage(uint32_t x, uint32_t keep, uint32_t rot)
 {
-    // value of lane (l ^ J), inside each half of 32 lanes: ds_swizzle in bit-mask mode (and 0x1f, or 0, xor J)
-    return (uint32_t)__builtin_amdgcn_ds_swizzle((int)v, 0x1F | (J << 10));
+    const uint32_t other = row_xor<J>(x);
+    const uint32_t moved = __builtin_amdgcn_alignbit(other, other, rot);
+    return (x & keep) | (moved & ~keep);
 }
 
-// One stage of the 32 x 32 bit-matrix transpose across 32 lanes: rows l and l ^ J exchange the bit
-// positions that have bit J set (lower row) / clear (upper row).
-template <int J>
-__device__ __forceinline__ uint32_t transpose_stage(uint32_t x, int lane)
+// Lane r of a row holds, in each 16-bit half, 16 bits of one column; returns, in lane r, bit r of the 16 columns
+// of the row (for each half).
+__device__ __forceinline__ uint32_t bit_transpose16(uint32_t x, const TransposeConsts &c)
 {
-    constexpr uint32_t M = J == 16 ? 0xFFFF0000u : J == 8 ? 0xFF00FF00u : J == 4 ? 0xF0F0F0F0u
-                         : J == 2 ? 0xCCCCCCCCu : 0xAAAAAAAAu;
-    const uint32_t other = lane_xor<J>(x);
-    const bool upper = (lane & J) != 0;
-    const uint32_t keep = upper ? M : ~M;               // bits this lane keeps
-    const uint32_t rot = __builtin_amdgcn_alignbit(other, other, upper ? J : 32 - J);   // >> J for the upper row, << J for the lower
-    return (x & keep) | (rot & ~keep);
-}
-
-// Lane c (of 32) holds the fixed-point value of column c; returns, in lane p, the packed word of plane p.
-__device__ __forceinline__ uint32_t bit_transpose32(uint32_t x, int lane)
-{
-    x = transpose_stage<16>(x, lane);
-    x = transpose_stage<8>(x, lane);
-    x = transpose_stage<4>(x, lane);
-    x = transpose_stage<2>(x, lane);
-    x = transpose_stage<1>(x, lane);
+    x = transpose_stage<8>(x, c.keep8, c.rot8);
+    x = transpose_stage<4>(x, c.keep4, c.rot4);
+    x = transpose_stage<2>(x, c.keep2, c.rot2);
+    x = transpose_stage<1>(x, c.keep1, c.rot1);
     return x;
 }
 
@@ -134,13 +157,22 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 template <int NQ>
 struct Cfg {
     static constexpr int RU = NQ >= 4 ? 2 : 8 / NQ;   // units (row tile, bitlayer) whose blocks are in flight per wave
+    // Units requested before the activations have arrived.  The memory pipeline of a CU serves requests in
+    // order, so the activation loads of the waves that start last queue behind every weight load issued before
+    // them: a small head start keeps HBM busy during the transpose, the rest of the ring follows once the planes
+    // are built (measured: requesting the whole ring first delays the first product by 1-4 us).
+    static constexpr int PRE = NQ >= 4 ? 1 : 2;
 };
 
 template <int NQ>
 __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
 {
-    constexpr int RU = Cfg<NQ>::RU;
+    constexpr int RU = Cfg<NQ>::RU, PRE = Cfg<NQ>::PRE;
     __shared__ int2 abuf[2][PB_MAX_BITS][kTileRows];   // (low 16 planes, high 16 planes) sums per bitlayer and row
+
+    // LDS sums start at zero (the only barrier that is not in step with the data: taken before any load is issued)
+    for (int i = threadIdx.x; i < 2 * PB_MAX_BITS * kTileRows; i += blockDim.x) (&abuf[0][0][0])[i] = make_int2(0, 0);
+    __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -153,6 +185,9 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
     const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
     const int U = rounds * m;
 
+    // layer scales, lane i holds scales[i]: the oldest load of the wave, so that no later wait is held up by it
+    const float scv = a.scales ? a.scales[lane < m ? lane : m - 1] : 0.0f;
+
     // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
     const size_t base_off = ((size_t)rt0 * a.cq + q0) * 1024;
     const char *base = reinterpret_cast<const char *>(a.packed) + base_off;
@@ -163,26 +198,28 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
     uint32_t ld_soff = 0;
     int ld_i = 0, ld_u = 0;
     auto issue = [&](u32x4 (&dst)[NQ]) {
-        const __amdgpu_buffer_rsrc_t rs =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, ld_u < U ? (int)avail : 0, 0x00020000);
+        // past the last unit, and for chunks beyond the end of a ragged last slice, the descriptor has 0 records:
+        // every lane is out of range, the load returns 0 and moves no data (no branch, so the compiler counts
+        // the loads in flight exactly)
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
-            if (q < nq) dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)ld_soff, /*nt*/ 2);
-            else dst[q] = u32x4{0, 0, 0, 0};
+            const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<char *>(base), 0, (ld_u < U && q < nq) ? (int)avail : 0, 0x00020000);
+            dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)ld_soff, /*nt*/ 2);
         }
         __builtin_amdgcn_sched_barrier(0x7);
         ++ld_u;
         if (++ld_i == m) { ld_i = 0; ld_soff += round_bytes - (uint32_t)(m - 1) * a.layer_bytes; }
         else ld_soff += a.layer_bytes;
     };
-#pragma unroll
-    for (int k = 0; k < RU; ++k) issue(ring[k]);
 
     // ---- the planes of this wave's slice, expanded to A operands, kept in registers ----
     // lane l = 16 * kb + p: planes p (lo) and 16 + p (hi) of the words 16 * q + 4 * kb + t
     const int kb = lane >> 4;
     u32x4 pa_lo[NQ][4], pa_hi[NQ][4];
     if (a.planes) {
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) issue(ring[k]);
         const uint32_t *pl = a.planes + ((size_t)n * 32 + (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
@@ -198,39 +235,60 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
         }
     } else {
         // Algorithm 2: x_q = Int(x * 2^f); then the bitwise transpose, 32 columns x 32 bits at a time in each
-        // half of the wave: lane (half H, column c) converts column c of word 16 q + 4 (2 H + e) + t.
-        const int C = a.cols0 + a.cols1;
-        const float *x0 = a.X0 + (size_t)n * a.cols0;
-        const float *x1 = a.X1 ? a.X1 + (size_t)n * a.cols1 : nullptr;
-        const int H = lane >> 5, c = lane & 31;
-        const bool odd = (kb & 1) != 0;
+        // half of the wave: lane (half H, column c) converts column c of word 16 q + 4 (2 H + e) + t, e = 0, 1.
+        // V_PERMLANE16_SWAP hands the even rows of 16 lanes both 16-column halves of the e = 0 word and the odd
+        // rows those of the e = 1 word, which is the first stage of the 32 x 32 transpose; the other four stages
+        // stay inside a row.  Lane (kb, p) ends with planes p and 16 + p of word 16 q + 4 kb + t.
+        // The activations are fetched before the weight stream starts, so that waiting for them does not wait
+        // for the weights (loads return in order); buffer loads return 0 beyond the end of a vector.
+        const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(a.X0 + (size_t)n * a.cols0), 0, a.cols0 * 4, 0x00020000);
+        const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(a.X1 ? a.X1 + (size_t)n * a.cols1 : a.X0), 0, a.X1 ? a.cols1 * 4 : 0, 0x00020000);
+        const int colb = (32 * (16 * q0 + 8 * (lane >> 5)) + (lane & 31)) * 4;   // byte offset of (q = 0, e = 0, t = 0)
+        uint32_t xv[NQ][4][2];
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            float xv[4][2];
+        for (int q = 0; q < NQ; ++q)
 #pragma unroll
             for (int t = 0; t < 4; ++t)
 #pragma unroll
                 for (int e = 0; e < 2; ++e) {
-                    const int col = 32 * (16 * (q0 + q) + 4 * (2 * H + e) + t) + c;
-                    float v = 0.0f;
-                    if (col < a.cols0) v = x0[col];
-                    else if (col < C) v = x1[col - a.cols0];
-                    xv[t][e] = v;
+                    xv[q][t][e] = __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
                 }
+        if (a.X1) {
+            // second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range
+            const int colb1 = colb - a.cols0 * 4;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int e = 0; e < 2; ++e)
+                        xv[q][t][e] |= __builtin_amdgcn_raw_buffer_load_b32(rx1, colb1 + 128 * (16 * q + 4 * e + t), 0, 0);
+        }
+        __builtin_amdgcn_sched_barrier(0x7);
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) issue(ring[k]);
+        const TransposeConsts tc = transpose_consts(lane);
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
 #pragma unroll
             for (int t = 0; t < 4; ++t) {
-                const uint32_t X =
-                    bit_transpose32((uint32_t)to_fixed_point(xv[t][0] * a.fscale, a.lim, a.lim_below, a.imax), lane);
-                const uint32_t Y =
-                    bit_transpose32((uint32_t)to_fixed_point(xv[t][1] * a.fscale, a.lim, a.lim_below, a.imax), lane);
-                // X: lane (H, p) has plane p of word (e = 0), Y: of word (e = 1).  Even kb keeps X's low plane and
-                // needs X's high plane from lane + 16; odd kb keeps Y's high plane and needs Y's low one from lane - 16.
-                const uint32_t recv = lane_xor<16>(odd ? X : Y);
-                expand_plane(odd ? recv : X, pa_lo[q][t]);
-                expand_plane(odd ? Y : recv, pa_hi[q][t]);
+                const uint32_t X = (uint32_t)to_fixed_point(__uint_as_float(xv[q][t][0]), a.fscale, a.imin, a.imax);
+                const uint32_t Y = (uint32_t)to_fixed_point(__uint_as_float(xv[q][t][1]), a.fscale, a.imin, a.imax);
+                const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
+                // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
+                const uint32_t c_lo = sw[0], c_hi = sw[1];
+                const uint32_t lo = (c_lo & 0xFFFFu) | (c_hi << 16);         // bits 0-15 of the 32 columns
+                const uint32_t hi = (c_hi & 0xFFFF0000u) | (c_lo >> 16);     // bits 16-31
+                expand_plane(bit_transpose16(lo, tc), pa_lo[q][t]);
+                expand_plane(bit_transpose16(hi, tc), pa_hi[q][t]);
             }
         }
     }
+    __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
+#pragma unroll
+    for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
     // per-lane plane weights: registers v of the low / high instruction hold planes 4 kb + v / 16 + 4 kb + v
     float kl[4], kh[4];
@@ -240,11 +298,6 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
         kh[v] = (kb == 3 && v == 3) ? -kl[v] : kl[v];    // plane 31 weighs -2^31 (Algorithm 2)
     }
 
-    // LDS sums start at zero
-    for (int i = threadIdx.x; i < 2 * PB_MAX_BITS * kTileRows; i += blockDim.x) (&abuf[0][0][0])[i] = make_int2(0, 0);
-    __syncthreads();
-
-    const float scv = a.scales ? a.scales[lane < m ? lane : m - 1] : 0.0f;   // lane i holds scales[i]
     const int j = lane & 15;
     int pi = 0, pr = 0;   // bitlayer and round of the unit being multiplied
     for (int u0 = 0; u0 < U; u0 += RU) {
@@ -254,7 +307,7 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
                 v4f acc_lo = {0.f, 0.f, 0.f, 0.f}, acc_hi = acc_lo;
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
-                    if (q < nq) {
+                    {   // (chunks beyond a ragged last slice multiply zero planes by zero weights)
                         const u32x4 w = ring[k][q];
                         v8i b;
                         b = weight_operand(w.x);
@@ -320,6 +373,24 @@ static int pick_nq(const Layout &L)
     return L.cq <= 16 ? 1 : 4;
 }
 
+// Workgroups of S waves that fit on the device at once (occupancy does not change while the process lives, so it
+// is looked up once per kernel variant and workgroup size).
+static int resident_workgroups(int nq, int S)
+{
+    static int cache[5][kMaxSlices + 1];
+    int v = __atomic_load_n(&cache[nq][S], __ATOMIC_RELAXED);
+    if (v > 0) return v;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    const void *fn = nq == 1 ? reinterpret_cast<const void *>(k_mfma<1>)
+                   : nq == 2 ? reinterpret_cast<const void *>(k_mfma<2>) : reinterpret_cast<const void *>(k_mfma<4>);
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, S * 64, 0) != hipSuccess) return 0;
+    v = cus * per_cu;
+    if (v > 0) __atomic_store_n(&cache[nq][S], v, __ATOMIC_RELAXED);
+    return v;
+}
+
 int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
                 int batch, float *Y, long long *A, hipStream_t st)
@@ -333,17 +404,18 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.m = bits_used;
     a.batch = batch;
     a.fscale = ldexpf(1.0f, frac_bits);
-    a.lim = ldexpf(1.0f, act_bits - 1);
-    a.lim_below = nextafterf(a.lim, 0.0f);
     a.imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
+    a.imin = -a.imax - 1;
     a.out_scale = ldexp(1.0, -frac_bits);
     const int nq = pick_nq(L);
     const int S = (L.cq + nq - 1) / nq;
     if (S > (nq == 1 ? 16 : 8)) return (int)hipErrorInvalidValue;
-    // workgroups: enough waves to fill the chip (16 per CU), each with whole row tiles
-    int target_waves = 4096;
-    if (const char *e = getenv("PB_TUNE_WAVES")) target_waves = atoi(e);
-    int wgs = target_waves / S;
+    // Workgroups: as many as are resident at once (so that every wave builds its planes once and the weight
+    // stream never waits for a second round of workgroups to start), each with whole row tiles.
+    int capacity = resident_workgroups(nq, S);
+    if (capacity < 1) return (int)hipErrorInvalidValue;
+    if (const char *e = getenv("PB_TUNE_WGS")) capacity = atoi(e);
+    int wgs = capacity / batch;
     if (wgs < 1) wgs = 1;
     if (wgs > L.rt_count) wgs = L.rt_count;
     a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
