@@ -164,20 +164,25 @@ struct Cfg {
     static constexpr int PRE = NQ >= 4 ? 1 : 2;
 };
 
-template <int NQ>
-__global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
+// NQ: chunks of 512 columns per wave; NV: activation vectors whose planes a wave keeps (each weight block is
+// expanded once and multiplied with all of them); MAXS: most waves (column slices) per workgroup, which bounds
+// the registers a wave may use.
+template <int NQ, int NV, int MAXS>
+__global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 {
     constexpr int RU = Cfg<NQ>::RU, PRE = Cfg<NQ>::PRE;
-    __shared__ int2 abuf[2][PB_MAX_BITS][kTileRows];   // (low 16 planes, high 16 planes) sums per bitlayer and row
+    // (low 16 planes, high 16 planes) sums per vector, bitlayer and row; two buffers, used by alternate row tiles
+    __shared__ int2 abuf[2][NV][PB_MAX_BITS][kTileRows];
 
     // LDS sums start at zero (the only barrier that is not in step with the data: taken before any load is issued)
-    for (int i = threadIdx.x; i < 2 * PB_MAX_BITS * kTileRows; i += blockDim.x) (&abuf[0][0][0])[i] = make_int2(0, 0);
+    for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * kTileRows; i += blockDim.x)
+        (&abuf[0][0][0][0])[i] = make_int2(0, 0);
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
-    const int n = blockIdx.y;
+    const int n0 = blockIdx.y * NV;                             // first activation vector of this workgroup
     const int m = a.m;
     const int q0 = wave * NQ;                                   // first chunk of this wave's column slice
     const int nq = min(NQ, a.cq - q0);                          // chunks it really has (>= 1 by construction)
@@ -216,22 +221,28 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
     // ---- the planes of this wave's slice, expanded to A operands, kept in registers ----
     // lane l = 16 * kb + p: planes p (lo) and 16 + p (hi) of the words 16 * q + 4 * kb + t
     const int kb = lane >> 4;
-    u32x4 pa_lo[NQ][4], pa_hi[NQ][4];
+    u32x4 pa_lo[NV][NQ][4], pa_hi[NV][NQ][4];
     if (a.planes) {
 #pragma unroll
         for (int k = 0; k < PRE; ++k) issue(ring[k]);
-        const uint32_t *pl = a.planes + ((size_t)n * 32 + (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
-            if (q < nq) {
-                lo = *reinterpret_cast<const uint4 *>(pl + q * 16);
-                hi = *reinterpret_cast<const uint4 *>(pl + (size_t)16 * a.cwp + q * 16);
+        for (int v = 0; v < NV; ++v) {
+            const int n = min(n0 + v, a.batch - 1);
+            const bool live = n0 + v < a.batch;
+            const uint32_t *pl =
+                a.planes + ((size_t)n * 32 + (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+                if (q < nq && live) {
+                    lo = *reinterpret_cast<const uint4 *>(pl + q * 16);
+                    hi = *reinterpret_cast<const uint4 *>(pl + (size_t)16 * a.cwp + q * 16);
+                }
+                expand_plane(lo.x, pa_lo[v][q][0]); expand_plane(lo.y, pa_lo[v][q][1]);
+                expand_plane(lo.z, pa_lo[v][q][2]); expand_plane(lo.w, pa_lo[v][q][3]);
+                expand_plane(hi.x, pa_hi[v][q][0]); expand_plane(hi.y, pa_hi[v][q][1]);
+                expand_plane(hi.z, pa_hi[v][q][2]); expand_plane(hi.w, pa_hi[v][q][3]);
             }
-            expand_plane(lo.x, pa_lo[q][0]); expand_plane(lo.y, pa_lo[q][1]);
-            expand_plane(lo.z, pa_lo[q][2]); expand_plane(lo.w, pa_lo[q][3]);
-            expand_plane(hi.x, pa_hi[q][0]); expand_plane(hi.y, pa_hi[q][1]);
-            expand_plane(hi.z, pa_hi[q][2]); expand_plane(hi.w, pa_hi[q][3]);
         }
     } else {
         // Algorithm 2: x_q = Int(x * 2^f); then the bitwise transpose, 32 columns x 32 bits at a time in each
@@ -240,62 +251,77 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
         // rows those of the e = 1 word, which is the first stage of the 32 x 32 transpose; the other four stages
         // stay inside a row.  Lane (kb, p) ends with planes p and 16 + p of word 16 q + 4 kb + t.
         // The activations are fetched before the weight stream starts, so that waiting for them does not wait
-        // for the weights (loads return in order); buffer loads return 0 beyond the end of a vector.
-        const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(a.X0 + (size_t)n * a.cols0), 0, a.cols0 * 4, 0x00020000);
-        const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
-            const_cast<float *>(a.X1 ? a.X1 + (size_t)n * a.cols1 : a.X0), 0, a.X1 ? a.cols1 * 4 : 0, 0x00020000);
+        // for the weights (loads return in order); buffer loads return 0 beyond the end of a vector, and for
+        // the vectors beyond the end of the batch.
         const int colb = (32 * (16 * q0 + 8 * (lane >> 5)) + (lane & 31)) * 4;   // byte offset of (q = 0, e = 0, t = 0)
-        uint32_t xv[NQ][4][2];
+        uint32_t xv[NV][NQ][4][2];
 #pragma unroll
-        for (int q = 0; q < NQ; ++q)
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int e = 0; e < 2; ++e) {
-                    xv[q][t][e] = __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
-                }
-        if (a.X1) {
-            // second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range
-            const int colb1 = colb - a.cols0 * 4;
+        for (int v = 0; v < NV; ++v) {
+            const int n = min(n0 + v, a.batch - 1);
+            const bool live = n0 + v < a.batch;
+            const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
+                const_cast<float *>(a.X0 + (size_t)n * a.cols0), 0, live ? a.cols0 * 4 : 0, 0x00020000);
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int t = 0; t < 4; ++t)
 #pragma unroll
                     for (int e = 0; e < 2; ++e)
-                        xv[q][t][e] |= __builtin_amdgcn_raw_buffer_load_b32(rx1, colb1 + 128 * (16 * q + 4 * e + t), 0, 0);
+                        xv[v][q][t][e] =
+                            __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
+        }
+        if (a.X1) {
+            // second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range
+            const int colb1 = colb - a.cols0 * 4;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                const int n = min(n0 + v, a.batch - 1);
+                const bool live = n0 + v < a.batch;
+                const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<float *>(a.X1 + (size_t)n * a.cols1), 0, live ? a.cols1 * 4 : 0, 0x00020000);
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            xv[v][q][t][e] |=
+                                __builtin_amdgcn_raw_buffer_load_b32(rx1, colb1 + 128 * (16 * q + 4 * e + t), 0, 0);
+            }
         }
         __builtin_amdgcn_sched_barrier(0x7);
 #pragma unroll
         for (int k = 0; k < PRE; ++k) issue(ring[k]);
         const TransposeConsts tc = transpose_consts(lane);
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
+        for (int v = 0; v < NV; ++v)
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const uint32_t X = (uint32_t)to_fixed_point(__uint_as_float(xv[q][t][0]), a.fscale, a.imin, a.imax);
-                const uint32_t Y = (uint32_t)to_fixed_point(__uint_as_float(xv[q][t][1]), a.fscale, a.imin, a.imax);
-                const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
-                // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
-                const uint32_t c_lo = sw[0], c_hi = sw[1];
-                const uint32_t lo = (c_lo & 0xFFFFu) | (c_hi << 16);         // bits 0-15 of the 32 columns
-                const uint32_t hi = (c_hi & 0xFFFF0000u) | (c_lo >> 16);     // bits 16-31
-                expand_plane(bit_transpose16(lo, tc), pa_lo[q][t]);
-                expand_plane(bit_transpose16(hi, tc), pa_hi[q][t]);
-            }
-        }
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t X =
+                        (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][0]), a.fscale, a.imin, a.imax);
+                    const uint32_t Y =
+                        (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][1]), a.fscale, a.imin, a.imax);
+                    const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
+                    // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
+                    const uint32_t c_lo = sw[0], c_hi = sw[1];
+                    const uint32_t lo = (c_lo & 0xFFFFu) | (c_hi << 16);         // bits 0-15 of the 32 columns
+                    const uint32_t hi = (c_hi & 0xFFFF0000u) | (c_lo >> 16);     // bits 16-31
+                    expand_plane(bit_transpose16(lo, tc), pa_lo[v][q][t]);
+                    expand_plane(bit_transpose16(hi, tc), pa_hi[v][q][t]);
+                }
     }
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
-    // per-lane plane weights: registers v of the low / high instruction hold planes 4 kb + v / 16 + 4 kb + v
+    // per-lane plane weights: registers c of the low / high instruction hold planes 4 kb + c / 16 + 4 kb + c
     float kl[4], kh[4];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-        kl[v] = (float)(1 << (4 * kb + v));
-        kh[v] = (kb == 3 && v == 3) ? -kl[v] : kl[v];    // plane 31 weighs -2^31 (Algorithm 2)
+    for (int c = 0; c < 4; ++c) {
+        kl[c] = (float)(1 << (4 * kb + c));
+        kh[c] = (kb == 3 && c == 3) ? -kl[c] : kl[c];    // plane 31 weighs -2^31 (Algorithm 2)
     }
 
     const int j = lane & 15;
@@ -304,53 +330,57 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
 #pragma unroll
         for (int k = 0; k < RU; ++k) {
             if (u0 + k < U) {
-                v4f acc_lo = {0.f, 0.f, 0.f, 0.f}, acc_hi = acc_lo;
+                v4f acc_lo[NV], acc_hi[NV];
+#pragma unroll
+                for (int v = 0; v < NV; ++v) acc_lo[v] = acc_hi[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                // (chunks beyond a ragged last slice multiply zero planes by zero weights)
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
-                    {   // (chunks beyond a ragged last slice multiply zero planes by zero weights)
-                        const u32x4 w = ring[k][q];
-                        v8i b;
-                        b = weight_operand(w.x);
-                        acc_lo = mfma_fp4(as_operand(pa_lo[q][0]), b, acc_lo);
-                        acc_hi = mfma_fp4(as_operand(pa_hi[q][0]), b, acc_hi);
-                        b = weight_operand(w.y);
-                        acc_lo = mfma_fp4(as_operand(pa_lo[q][1]), b, acc_lo);
-                        acc_hi = mfma_fp4(as_operand(pa_hi[q][1]), b, acc_hi);
-                        b = weight_operand(w.z);
-                        acc_lo = mfma_fp4(as_operand(pa_lo[q][2]), b, acc_lo);
-                        acc_hi = mfma_fp4(as_operand(pa_hi[q][2]), b, acc_hi);
-                        b = weight_operand(w.w);
-                        acc_lo = mfma_fp4(as_operand(pa_lo[q][3]), b, acc_lo);
-                        acc_hi = mfma_fp4(as_operand(pa_hi[q][3]), b, acc_hi);
+                    const u32x4 w = ring[k][q];
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        const v8i b = weight_operand(w[t]);
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) {
+                            acc_lo[v] = mfma_fp4(as_operand(pa_lo[v][q][t]), b, acc_lo[v]);
+                            acc_hi[v] = mfma_fp4(as_operand(pa_hi[v][q][t]), b, acc_hi[v]);
+                        }
                     }
                 }
                 // plane weighting inside the lane.  Counts are <= 2048 (a slice has at most 2048 columns), so
                 // c0 + 2 c1 + 4 c2 +- 8 c3 < 2^15 and its multiple by 2^(4 kb) is exact in fp32 and < 2^27.
-                const float lo_f = acc_lo[0] * kl[0] + acc_lo[1] * kl[1] + acc_lo[2] * kl[2] + acc_lo[3] * kl[3];
-                const float hi_f = acc_hi[0] * kh[0] + acc_hi[1] * kh[1] + acc_hi[2] * kh[2] + acc_hi[3] * kh[3];
-                int2 *dst = &abuf[pr & 1][pi][j];
-                atomicAdd(&dst->x, (int)lo_f);
-                atomicAdd(&dst->y, (int)hi_f);
+#pragma unroll
+                for (int v = 0; v < NV; ++v) {
+                    const float lo_f = acc_lo[v][0] * kl[0] + acc_lo[v][1] * kl[1] + acc_lo[v][2] * kl[2] +
+                                       acc_lo[v][3] * kl[3];
+                    const float hi_f = acc_hi[v][0] * kh[0] + acc_hi[v][1] * kh[1] + acc_hi[v][2] * kh[2] +
+                                       acc_hi[v][3] * kh[3];
+                    int2 *dst = &abuf[pr & 1][v][pi][j];
+                    atomicAdd(&dst->x, (int)lo_f);
+                    atomicAdd(&dst->y, (int)hi_f);
+                }
                 if (++pi == m) {
-                    // the row tile is complete in every slice: one wave (taking turns) scales and stores it
+                    // the row tile is complete in every slice: one wave (taking turns) scales and stores it,
+                    // lane = (vector, row)
                     pi = 0;
                     __syncthreads();
-                    if (wave == pr % nwaves && lane < kTileRows) {
-                        const int row = (rt0 + pr) * kTileRows + lane;
-                        int2 *src = &abuf[pr & 1][0][lane];
+                    const int v = lane >> 4, n = n0 + v;
+                    if (wave == pr % nwaves && v < NV && n < a.batch) {
+                        const int row = (rt0 + pr) * kTileRows + j;
+                        int2 *src = &abuf[pr & 1][v < NV ? v : 0][0][j];
                         double z = 0.0;
                         for (int i = 0; i < m; ++i) {
-                            const int2 v = src[i * kTileRows];
+                            const int2 s = src[i * kTileRows];
                             src[i * kTileRows] = make_int2(0, 0);
                             // A_i = lo + hi * 2^16 exactly: lo < 2^31 (unsigned), |hi| <= 2^30
                             if (a.A) {
                                 if (row < a.R)
                                     a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
-                                        (long long)(uint32_t)v.x + ((long long)v.y << 16);
+                                        (long long)(uint32_t)s.x + ((long long)s.y << 16);
                             } else {
                                 const float si =
                                     __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(scv), i));
-                                z += (double)si * ((double)(uint32_t)v.x + (double)v.y * 65536.0);
+                                z += (double)si * ((double)(uint32_t)s.x + (double)s.y * 65536.0);
                             }
                         }
                         if (!a.A && row < a.R) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
@@ -363,31 +393,53 @@ __global__ __launch_bounds__(NQ == 1 ? 1024 : 512) void k_mfma(const MfmaArgs a)
     }
 }
 
-static int pick_nq(const Layout &L)
+// The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup).
+struct Variant {
+    int nq, nv, maxs;
+    const void *fn;
+};
+#define PB_VARIANT(NQ, NV, MAXS) {NQ, NV, MAXS, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS>)}
+static const Variant kVariants[] = {
+    PB_VARIANT(1, 1, 16), PB_VARIANT(1, 2, 8), PB_VARIANT(1, 4, 8),
+    PB_VARIANT(2, 1, 8),  PB_VARIANT(2, 2, 8),
+    PB_VARIANT(4, 1, 8),
+};
+constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+
+// As many vectors per wave as the batch has and the registers allow (each weight block is then read and expanded
+// once for all of them), then the smallest slice (most waves per row, shortest transpose per wave) whose slice
+// count fits a workgroup.
+static int pick_variant(const Layout &L, int batch)
 {
-    // smallest slice (most waves per row, shortest transpose per wave) whose slice count fits a workgroup
-    if (const char *e = getenv("PB_TUNE_NQ")) {
-        int v = atoi(e);
-        if ((v == 1 || v == 2 || v == 4) && (L.cq + v - 1) / v <= (v == 1 ? 16 : 8)) return v;
+    int want_nq = 0, want_nv = 0;
+    if (const char *e = getenv("PB_TUNE_NQ")) want_nq = atoi(e);
+    if (const char *e = getenv("PB_TUNE_NV")) want_nv = atoi(e);
+    int best = -1;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if ((L.cq + v.nq - 1) / v.nq > v.maxs) continue;
+        if (want_nq && v.nq != want_nq) continue;
+        if (want_nv ? v.nv != want_nv : (v.nv > 1 && v.nv / 2 >= batch)) continue;   // no more than one empty half
+        if (best < 0 || v.nv > kVariants[best].nv || (v.nv == kVariants[best].nv && v.nq < kVariants[best].nq))
+            best = i;
     }
-    return L.cq <= 16 ? 1 : 4;
+    return best;
 }
 
 // Workgroups of S waves that fit on the device at once (occupancy does not change while the process lives, so it
 // is looked up once per kernel variant and workgroup size).
-static int resident_workgroups(int nq, int S)
+static int resident_workgroups(int variant, int S)
 {
-    static int cache[5][kMaxSlices + 1];
-    int v = __atomic_load_n(&cache[nq][S], __ATOMIC_RELAXED);
+    static int cache[kNumVariants][kMaxSlices + 1];
+    int v = __atomic_load_n(&cache[variant][S], __ATOMIC_RELAXED);
     if (v > 0) return v;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    const void *fn = nq == 1 ? reinterpret_cast<const void *>(k_mfma<1>)
-                   : nq == 2 ? reinterpret_cast<const void *>(k_mfma<2>) : reinterpret_cast<const void *>(k_mfma<4>);
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, S * 64, 0) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kVariants[variant].fn, S * 64, 0) != hipSuccess)
+        return 0;
     v = cus * per_cu;
-    if (v > 0) __atomic_store_n(&cache[nq][S], v, __ATOMIC_RELAXED);
+    if (v > 0) __atomic_store_n(&cache[variant][S], v, __ATOMIC_RELAXED);
     return v;
 }
 
@@ -407,26 +459,25 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
     a.imin = -a.imax - 1;
     a.out_scale = ldexp(1.0, -frac_bits);
-    const int nq = pick_nq(L);
-    const int S = (L.cq + nq - 1) / nq;
-    if (S > (nq == 1 ? 16 : 8)) return (int)hipErrorInvalidValue;
+    const int vi = pick_variant(L, batch);
+    if (vi < 0) return (int)hipErrorInvalidValue;
+    const Variant &var = kVariants[vi];
+    const int S = (L.cq + var.nq - 1) / var.nq;
+    const int groups = (batch + var.nv - 1) / var.nv;
     // Workgroups: as many as are resident at once (so that every wave builds its planes once and the weight
     // stream never waits for a second round of workgroups to start), each with whole row tiles.
-    int capacity = resident_workgroups(nq, S);
+    int capacity = resident_workgroups(vi, S);
     if (capacity < 1) return (int)hipErrorInvalidValue;
     if (const char *e = getenv("PB_TUNE_WGS")) capacity = atoi(e);
-    int wgs = capacity / batch;
+    int wgs = capacity / groups;
     if (wgs < 1) wgs = 1;
     if (wgs > L.rt_count) wgs = L.rt_count;
     a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
-    const dim3 grid((unsigned)wgs, (unsigned)batch), block((unsigned)S * 64);
-    switch (nq) {
-        case 1: hipLaunchKernelGGL(k_mfma<1>, grid, block, 0, st, a); break;
-        case 2: hipLaunchKernelGGL(k_mfma<2>, grid, block, 0, st, a); break;
-        default: hipLaunchKernelGGL(k_mfma<4>, grid, block, 0, st, a); break;
-    }
-    return (int)hipGetLastError();
+    void *args[] = {&a};
+    const hipError_t e = hipLaunchKernel(var.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
+                                         0, st);
+    return (int)(e != hipSuccess ? e : hipGetLastError());
 }
 
 }  // namespace pb

@@ -87,6 +87,14 @@ def test_activation_distributions(pb, layout, xdist):
     run_layer(pb, W, 4, X, [1, 4], layout=layout)
 
 
+@pytest.mark.parametrize("shape_batch", [(40, 700, 5), (33, 4096, 7), (20, 5000, 3), (18, 8192, 6), (17, 9000, 2)])
+def test_batches_that_do_not_fill_a_vector_group(pb, layout, shape_batch):
+    R, C, N = shape_batch
+    W, X = synth.ragged(R, C, batch=N, case=11, xdist="normal")
+    print("batch", shape_batch, flush=True)
+    run_layer(pb, W, 3, X, [1, 3], layout=layout)
+
+
 def test_fixed_point_conversion(pb):
     u = 2.0 ** -16
     special = [0.0, 1.0, -2.0, 0.5 * u, -0.5 * u, 1.5 * u, -1.5 * u, 1.0 - 2.0 ** -24, 32767.998046875, 32768.0,
