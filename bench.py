@@ -44,6 +44,10 @@ def parse():
     ap.add_argument("--warm", action="store_true", help="reuse one weight copy (cache-resident) instead of the pool")
     ap.add_argument("--eager", action="store_true", help="plain launches from Python instead of HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--no-batch", action="store_true", help="skip the batched (8192 x 8192, batch 1..64) comparison")
+    ap.add_argument("--calib", action="store_true",
+                    help="also launch a plain elementwise kernel that reads and writes 256 MiB (reference for the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
     ap.add_argument("--detail", default=None, help="also write the JSON (indented) to this file")
     return ap.parse_args()
 
@@ -196,6 +200,18 @@ def main():
     binding["kernel"] = other["kernel"] = "k_mfma" if mfma else "k_matvec"
     binding["avg_launch_us"] = other["avg_launch_us"] = round(avg_kernel_s * 1e6, 3)
     binding["active_planes"] = nplanes
+    binding["algorithmic_bytes_per_launch"] = int(avg_bytes)
+    # measured HBM traffic per launch (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a copy kernel of known size):
+    # taken from the committed counter summary of this kernel and workload, if there is one
+    roof_hbm["traffic"] = measured_traffic("k_mfma" if mfma else "k_matvec", n, B)
+
+    if args.calib:
+        xc = torch.zeros(64 << 20, dtype=torch.float32, device=dev)
+        yc = torch.empty_like(xc)
+        for _ in range(4):
+            torch.add(xc, 1.0, out=yc)      # one elementwise kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del xc, yc
 
     out = {
         "metric": "effective weight GB/s + matvecs/sec at bits_used=1..8 (batch 1); % HBM roofline",
@@ -227,6 +243,10 @@ def main():
         "roofline_other": other,
     }
 
+    if not args.no_batch:
+        del pool, packed
+        torch.cuda.empty_cache()
+        out["batch_sweep"] = batch_sweep(torch, pb, synth, dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(W, X, B, layer_bytes)
 
@@ -235,6 +255,59 @@ def main():
         with open(args.detail, "w") as f:
             json.dump(out, f, indent=1)
     print(line, flush=True)
+
+
+def measured_traffic(kernel, n, B):
+    """HBM bytes per launch from profiles/<kernel>_fc<n>_b<B>_pmc.txt (line 'traffic_bytes_per_launch: N'), else None."""
+    path = os.path.join(ROOT, "profiles", "%s_fc%d_b%d_pmc.txt" % (kernel, n, B))
+    try:
+        with open(path) as f:
+            for line in f:
+                if line.startswith("traffic_bytes_per_launch:"):
+                    return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
+
+
+def batch_sweep(torch, pb, synth, dev):
+    """Large FC layer (8192 x 8192, B = 8, bits_used = 8) at batch 1, 4, 16, 64: the regime where the product is a
+    dense contraction.  Both kernels, weights warm (the 64 MiB stay in the last-level cache between the passes
+    of one call anyway).  Work = rows * cols * bits_used * 32 planes * batch 1-bit multiply-accumulates."""
+    n, B, m = 8192, 8, 8
+    W, _ = synth.fc_square(n, 0.01, batch=1, cfg=5)
+    Wd = torch.from_numpy(W).to(dev)
+    del W
+    rows = []
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(200300822 + 5000)
+    X = torch.randn((64, n), device=dev, generator=gen)
+    Y = torch.empty((64, n), dtype=torch.float32, device=dev)
+    for name, lay in (("mfma", pb.PB_LAYOUT_TILE16_V1), ("popc", pb.PB_LAYOUT_ROWMAJOR_V1)):
+        lin = pb.PackedLinear(Wd, B, max_batch=64, layout=lay)
+        for N in (1, 4, 16, 64):
+            def f():
+                pb.pb_matmul(lin.packed, lin.scales, lin.desc, m, X[:N], N, Y[:N], lin.workspace)
+            for _ in range(2):
+                f()
+            reps = 20 if N <= 16 else 4
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                f()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / reps
+            macs = float(n) * n * m * 32 * N
+            row = {"kernel": name, "batch": N, "us_per_call": round(t * 1e6, 1),
+                   "us_per_vector": round(t * 1e6 / N, 2), "Tbitmac_per_s": round(macs / t / 1e12, 1)}
+            if name == "mfma":
+                row["mfma_frac"] = round(2 * macs / t / 1e12 / FP4_PEAK_TFLOPS, 4)
+            rows.append(row)
+        del lin
+    return {"workload": "FC 8192x8192, B=8, bits_used=8, x~N(0,1), batch 1/4/16/64, weights warm", "rows": rows}
 
 
 def cpu_baseline(W, X, B, layer_bytes):
