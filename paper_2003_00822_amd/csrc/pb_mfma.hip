@@ -154,29 +154,28 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, 0x7F, 0, 0x7F);
 }
 
-template <int NQ>
-struct Cfg {
-    static constexpr int RU = NQ >= 4 ? 2 : 8 / NQ;   // units (row tile, bitlayer) whose blocks are in flight per wave
+// NQ: chunks of 512 columns per wave; NV: activation vectors whose planes a wave keeps (each weight block is
+// expanded once and multiplied with all of them); MAXS: most waves (column slices) per workgroup, which bounds
+// the registers a wave may use; RU: units (row tile, bitlayer) whose blocks a wave has in flight.  The host picks
+// RU <= the units a wave has, so that a short stream pays for no empty ring slots; 4 KB in flight per wave
+// measured best (more requests in flight than that slow the short streams down and do not speed up the long ones).
+template <int NQ, int NV, int MAXS, int RU>
+__global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
+{
     // Units requested before the activations have arrived.  The memory pipeline of a CU serves requests in
     // order, so the activation loads of the waves that start last queue behind every weight load issued before
     // them: a small head start keeps HBM busy during the transpose, the rest of the ring follows once the planes
-    // are built (measured: requesting the whole ring first delays the first product by 1-4 us).
-    static constexpr int PRE = NQ >= 4 ? 1 : 2;
-};
-
-// NQ: chunks of 512 columns per wave; NV: activation vectors whose planes a wave keeps (each weight block is
-// expanded once and multiplied with all of them); MAXS: most waves (column slices) per workgroup, which bounds
-// the registers a wave may use.
-template <int NQ, int NV, int MAXS>
-__global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
-{
-    constexpr int RU = Cfg<NQ>::RU, PRE = Cfg<NQ>::PRE;
+    // are built.
+    constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
+    constexpr int LS = 4 / NV;   // lanes (groups of 16) that share the bitlayers of one vector in the final sum
     // (low 16 planes, high 16 planes) sums per vector, bitlayer and row; two buffers, used by alternate row tiles
     __shared__ int2 abuf[2][NV][PB_MAX_BITS][kTileRows];
+    __shared__ float s_scales[PB_MAX_BITS];
 
     // LDS sums start at zero (the only barrier that is not in step with the data: taken before any load is issued)
     for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * kTileRows; i += blockDim.x)
         (&abuf[0][0][0][0])[i] = make_int2(0, 0);
+    if (threadIdx.x < PB_MAX_BITS) s_scales[threadIdx.x] = (a.scales && (int)threadIdx.x < a.m) ? a.scales[threadIdx.x] : 0.0f;
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -189,9 +188,6 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int rt0 = blockIdx.x * a.rounds_per_wg;
     const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
     const int U = rounds * m;
-
-    // layer scales, lane i holds scales[i]: the oldest load of the wave, so that no later wait is held up by it
-    const float scv = a.scales ? a.scales[lane < m ? lane : m - 1] : 0.0f;
 
     // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
     const size_t base_off = ((size_t)rt0 * a.cq + q0) * 1024;
@@ -360,30 +356,34 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     atomicAdd(&dst->y, (int)hi_f);
                 }
                 if (++pi == m) {
-                    // the row tile is complete in every slice: one wave (taking turns) scales and stores it,
-                    // lane = (vector, row)
+                    // The row tile is complete in every slice: one wave (taking turns) scales and stores it.
+                    // Lane = (group g of 16, row j); group g works on vector g % NV and on the bitlayers
+                    // g / NV, g / NV + LS, ...; the LS partial sums of a vector are then added across groups.
                     pi = 0;
                     __syncthreads();
-                    const int v = lane >> 4, n = n0 + v;
-                    if (wave == pr % nwaves && v < NV && n < a.batch) {
+                    if (wave == pr % nwaves) {
+                        const int g = lane >> 4, v = g % NV, n = n0 + v;
                         const int row = (rt0 + pr) * kTileRows + j;
-                        int2 *src = &abuf[pr & 1][v < NV ? v : 0][0][j];
+                        const bool live = n < a.batch && row < a.R;
                         double z = 0.0;
-                        for (int i = 0; i < m; ++i) {
-                            const int2 s = src[i * kTileRows];
-                            src[i * kTileRows] = make_int2(0, 0);
+                        for (int i = g / NV; i < m; i += LS) {
+                            int2 *src = &abuf[pr & 1][v][i][j];
+                            const int2 s = *src;
+                            *src = make_int2(0, 0);
                             // A_i = lo + hi * 2^16 exactly: lo < 2^31 (unsigned), |hi| <= 2^30
                             if (a.A) {
-                                if (row < a.R)
+                                if (live)
                                     a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
                                         (long long)(uint32_t)s.x + ((long long)s.y << 16);
                             } else {
-                                const float si =
-                                    __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(scv), i));
-                                z += (double)si * ((double)(uint32_t)s.x + (double)s.y * 65536.0);
+                                z += (double)s_scales[i] * ((double)(uint32_t)s.x + (double)s.y * 65536.0);
                             }
                         }
-                        if (!a.A && row < a.R) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
+                        if (!a.A) {
+                            if (LS >= 2) z += __shfl_xor(z, 16 * NV, 64);
+                            if (LS >= 4) z += __shfl_xor(z, 32, 64);
+                            if (live && g < NV) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
+                        }
                     }
                     ++pr;
                 }
@@ -393,22 +393,25 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     }
 }
 
-// The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup).
+// The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup, ring depth in units).
 struct Variant {
-    int nq, nv, maxs;
+    int nq, nv, maxs, ru;
     const void *fn;
 };
-#define PB_VARIANT(NQ, NV, MAXS) {NQ, NV, MAXS, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS>)}
+#define PB_VARIANT(NQ, NV, MAXS, RU) {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU>)}
 static const Variant kVariants[] = {
-    PB_VARIANT(1, 1, 16), PB_VARIANT(1, 2, 8), PB_VARIANT(1, 4, 8),
-    PB_VARIANT(2, 1, 8),  PB_VARIANT(2, 2, 8),
-    PB_VARIANT(4, 1, 8),
+    PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
+    PB_VARIANT(1, 2, 8, 1),  PB_VARIANT(1, 2, 8, 2),  PB_VARIANT(1, 2, 8, 4),
+    PB_VARIANT(1, 4, 8, 1),  PB_VARIANT(1, 4, 8, 2),  PB_VARIANT(1, 4, 8, 4),
+    PB_VARIANT(2, 1, 8, 1),  PB_VARIANT(2, 1, 8, 2),
+    PB_VARIANT(2, 2, 8, 1),  PB_VARIANT(2, 2, 8, 2),
+    PB_VARIANT(4, 1, 8, 1),  PB_VARIANT(4, 1, 8, 2),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
 // As many vectors per wave as the batch has and the registers allow (each weight block is then read and expanded
 // once for all of them), then the smallest slice (most waves per row, shortest transpose per wave) whose slice
-// count fits a workgroup.
+// count fits a workgroup; ring depth 1 (the deeper rings are picked once the units per wave are known).
 static int pick_variant(const Layout &L, int batch)
 {
     int want_nq = 0, want_nv = 0;
@@ -417,11 +420,26 @@ static int pick_variant(const Layout &L, int batch)
     int best = -1;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
+        if (v.ru != 1) continue;
         if ((L.cq + v.nq - 1) / v.nq > v.maxs) continue;
         if (want_nq && v.nq != want_nq) continue;
         if (want_nv ? v.nv != want_nv : (v.nv > 1 && v.nv / 2 >= batch)) continue;   // no more than one empty half
         if (best < 0 || v.nv > kVariants[best].nv || (v.nv == kVariants[best].nv && v.nq < kVariants[best].nq))
             best = i;
+    }
+    return best;
+}
+
+// The sibling of variant `vi` with the deepest ring that a wave with `units` units fills.
+static int pick_ring(int vi, int units)
+{
+    int want = 0;
+    if (const char *e = getenv("PB_TUNE_RU")) want = atoi(e);
+    int best = vi;
+    for (int i = 0; i < kNumVariants; ++i) {
+        const Variant &v = kVariants[i];
+        if (v.nq != kVariants[vi].nq || v.nv != kVariants[vi].nv) continue;
+        if (want ? v.ru == want : (v.ru <= units && v.ru > kVariants[best].ru)) best = i;
     }
     return best;
 }
@@ -459,14 +477,14 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
     a.imin = -a.imax - 1;
     a.out_scale = ldexp(1.0, -frac_bits);
-    const int vi = pick_variant(L, batch);
+    int vi = pick_variant(L, batch);
     if (vi < 0) return (int)hipErrorInvalidValue;
-    const Variant &var = kVariants[vi];
+    const Variant &var = kVariants[vi];   // (the ring depth does not change a variant's occupancy: same registers +- a few)
     const int S = (L.cq + var.nq - 1) / var.nq;
     const int groups = (batch + var.nv - 1) / var.nv;
     // Workgroups: as many as are resident at once (so that every wave builds its planes once and the weight
     // stream never waits for a second round of workgroups to start), each with whole row tiles.
-    int capacity = resident_workgroups(vi, S);
+    int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S);   // of the sibling that needs the most registers
     if (capacity < 1) return (int)hipErrorInvalidValue;
     if (const char *e = getenv("PB_TUNE_WGS")) capacity = atoi(e);
     int wgs = capacity / groups;
@@ -475,7 +493,7 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
     void *args[] = {&a};
-    const hipError_t e = hipLaunchKernel(var.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
+    const hipError_t e = hipLaunchKernel(kVariants[pick_ring(vi, a.rounds_per_wg * bits_used)].fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
                                          0, st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
 }
