@@ -90,14 +90,20 @@ inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L
     return true;
 }
 
-// Position (in words, inside one bitlayer) of word w of row r.
-__host__ __device__ inline size_t word_index(uint32_t layout, int cwp, int r, int w)
+// Strides (in words) of the tiled layout: between the bitlayers of one row tile and between row tiles.
+// (Bitlayer-major; keeping the bitlayers of a row tile next to each other instead measured the same speed.)
+inline size_t tile16_layer_stride(const Layout &L) { return L.layer_words; }
+inline size_t tile16_rowtile_stride(const Layout &L) { return (size_t)L.cq * 256; }
+
+// Position (in words) of word w of row r of bitlayer `layer`.
+__host__ __device__ inline size_t word_index(uint32_t layout, int cwp, size_t layer_words, int layer, int r, int w)
 {
-    if (layout == PB_LAYOUT_ROWMAJOR_V1) return (size_t)r * (size_t)cwp + (size_t)w;
-    const int cq = cwp / kChunkWords;
-    const size_t block = (size_t)(r / kTileRows) * (size_t)cq + (size_t)(w / kChunkWords);
+    if (layout == PB_LAYOUT_ROWMAJOR_V1) return (size_t)layer * layer_words + (size_t)r * (size_t)cwp + (size_t)w;
+    const size_t cq = (size_t)(cwp / kChunkWords);
     const int lane = ((w % kChunkWords) / 4) * kTileRows + (r % kTileRows);
-    return block * 256 + (size_t)lane * 4 + (size_t)(w % 4);
+    const size_t in_block = (size_t)lane * 4 + (size_t)(w % 4);
+    const size_t rt = (size_t)(r / kTileRows), q = (size_t)(w / kChunkWords);
+    return (size_t)layer * layer_words + (rt * cq + q) * 256 + in_block;
 }
 
 inline size_t packed_bytes(const Layout &L) { return L.layer_words * (size_t)L.bits * sizeof(uint32_t); }

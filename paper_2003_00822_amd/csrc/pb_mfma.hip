@@ -51,7 +51,7 @@ struct MfmaArgs {
     float *Y;
     long long *A;
     size_t packed_bytes;
-    uint32_t layer_bytes;
+    uint32_t layer_step, round_step;   // bytes from one bitlayer of a row tile to the next, from one row tile to the next
     int cols0, cols1;
     int R, rt_count, cq, cwp;
     int m;                      // bitlayers to accumulate
@@ -190,10 +190,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int U = rounds * m;
 
     // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
-    const size_t base_off = ((size_t)rt0 * a.cq + q0) * 1024;
+    const size_t base_off = (size_t)rt0 * a.round_step + (size_t)q0 * 1024;
     const char *base = reinterpret_cast<const char *>(a.packed) + base_off;
     const uint32_t avail = (uint32_t)(a.packed_bytes - base_off);
-    const uint32_t round_bytes = (uint32_t)a.cq * 1024;
     const int voff = lane * 16;
     u32x4 ring[RU][NQ];
     uint32_t ld_soff = 0;
@@ -210,8 +209,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         }
         __builtin_amdgcn_sched_barrier(0x7);
         ++ld_u;
-        if (++ld_i == m) { ld_i = 0; ld_soff += round_bytes - (uint32_t)(m - 1) * a.layer_bytes; }
-        else ld_soff += a.layer_bytes;
+        if (++ld_i == m) { ld_i = 0; ld_soff += a.round_step - (uint32_t)(m - 1) * a.layer_step; }
+        else ld_soff += a.layer_step;
     };
 
     // ---- the planes of this wave's slice, expanded to A operands, kept in registers ----
@@ -470,7 +469,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     MfmaArgs a;
     a.packed = packed; a.X0 = X0; a.X1 = X1; a.planes = planes; a.scales = scales; a.Y = Y; a.A = A;
     a.packed_bytes = packed_bytes(L);
-    a.layer_bytes = (uint32_t)(L.layer_words * 4);
+    a.layer_step = (uint32_t)(tile16_layer_stride(L) * 4);
+    a.round_step = (uint32_t)(tile16_rowtile_stride(L) * 4);
     a.cols0 = cols0; a.cols1 = cols1;
     a.R = L.rows; a.rt_count = L.rt_count; a.cq = L.cq; a.cwp = L.cwp;
     a.m = bits_used;

@@ -78,10 +78,9 @@ __global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint3
                 if (i < bits) wd[i] |= ((u >> (bits - 1 - i)) & 1u) << b;
         }
     }
-    const size_t pos = word_index(layout, cwp, r, w);
 #pragma unroll
     for (int i = 0; i < PB_MAX_BITS; ++i)
-        if (i < bits) packed[(size_t)i * layer_words + pos] = wd[i];
+        if (i < bits) packed[word_index(layout, cwp, layer_words, i, r, w)] = wd[i];
 }
 
 // reads max|W| from scales[0] (where k_absmax left it) and writes the layer scales
@@ -103,9 +102,8 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
     int r = (int)(idx / (size_t)cols);
     int c = (int)(idx % (size_t)cols);
     uint32_t u = 0;
-    const size_t pos = word_index(layout, cwp, r, c >> 5);
     for (int i = 0; i < bits; ++i) {
-        uint32_t word = packed[(size_t)i * layer_words + pos];
+        uint32_t word = packed[word_index(layout, cwp, layer_words, i, r, c >> 5)];
         u |= ((word >> (c & 31)) & 1u) << (bits - 1 - i);
     }
     int32_t v = (int32_t)(u << (32 - bits)) >> (32 - bits);  // sign-extend the B-bit code

@@ -12,7 +12,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libpbatch.so")
+# PBATCH_LIB points the binding at another build of the same library (e.g. one compiled with other tuning macros)
+LIB_PATH = os.environ.get("PBATCH_LIB") or os.path.join(_HERE, "libpbatch.so")
 
 PB_OK, PB_EINVAL, PB_EALIGN, PB_ESIZE, PB_EHIP = 0, -1, -2, -3, -4
 PB_MAX_BITS = 16
