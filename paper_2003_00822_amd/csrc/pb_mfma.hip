@@ -175,7 +175,6 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     // LDS sums start at zero (the only barrier that is not in step with the data: taken before any load is issued)
     for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * kTileRows; i += blockDim.x)
         (&abuf[0][0][0][0])[i] = make_int2(0, 0);
-    if (threadIdx.x < PB_MAX_BITS) s_scales[threadIdx.x] = (a.scales && (int)threadIdx.x < a.m) ? a.scales[threadIdx.x] : 0.0f;
     __syncthreads();
 
     const int lane = threadIdx.x & 63;
@@ -188,6 +187,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int rt0 = blockIdx.x * a.rounds_per_wg;
     const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
     const int U = rounds * m;
+
+    // layer scales, lane i holds scales[i]: the oldest load of the wave, so that no later wait is held up by it;
+    // parked in LDS once the planes are built (the barrier before the first final sum orders that store)
+    const float scv = (a.scales && lane < m) ? a.scales[lane] : 0.0f;
 
     // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
     const size_t base_off = (size_t)rt0 * a.round_step + (size_t)q0 * 1024;
@@ -307,6 +310,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     expand_plane(bit_transpose16(hi, tc), pa_hi[v][q][t]);
                 }
     }
+    if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
