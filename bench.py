@@ -45,6 +45,7 @@ def parse():
     ap.add_argument("--eager", action="store_true", help="plain launches from Python instead of HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-batch", action="store_true", help="skip the batched (8192 x 8192, batch 1..64) comparison")
+    ap.add_argument("--no-sizes", action="store_true", help="skip the larger layers (8192, 16384: bandwidth asymptote)")
     ap.add_argument("--calib", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
@@ -89,7 +90,7 @@ def main():
     # Work lists.  A "round" visits every weight copy once: G = copies // B steps of B calls (bits_used 1..B).
     # Rounds are captured into HIP graphs so that the Python launch overhead (several microseconds per call,
     # more than a kernel lasts) is outside the measurement; --eager times plain launches instead.
-    G = max(1, copies // B)
+    G = max(1, copies // B) if not args.warm else 6
 
     def round_calls():
         i = 0
@@ -138,24 +139,26 @@ def main():
     # ---- per bits_used: whole call (prep + product) and the product kernel alone ----
     per_m = []
     kern_time_sum = 0.0
-    reps = max(2, -(-max(50, args.steps) // copies))
+    reps = max(2, -(-max(50, args.steps) // max(copies, 48)))
+
+    loop_calls = max(copies, 48)     # calls per captured graph (a graph launch costs several microseconds itself)
 
     def call_loop(m):
         def f():
-            for i in range(copies):
-                pb.pb_matmul(pool[i], scales, d, m, Xd, 1, Y, ws)
+            for i in range(loop_calls):
+                pb.pb_matmul(pool[i % copies], scales, d, m, Xd, 1, Y, ws)
         return f
 
     def kern_loop(m):
         def f():
-            for i in range(copies):
-                pb.pb_matmul_prepared(pool[i], scales, d, m, 1, Y, ws)
+            for i in range(loop_calls):
+                pb.pb_matmul_prepared(pool[i % copies], scales, d, m, 1, Y, ws)
         return f
 
     for m in range(1, B + 1):
-        t_call = timed(capture(call_loop(m)), reps) / copies
+        t_call = timed(capture(call_loop(m)), reps) / loop_calls
         # matrix-core layout: the call IS one kernel; popcount layout: the product kernel without the activation kernel
-        t_kern = t_call if mfma else timed(capture(kern_loop(m)), reps) / copies
+        t_kern = t_call if mfma else timed(capture(kern_loop(m)), reps) / loop_calls
         kern_time_sum += t_kern
         wbytes = layer_bytes * m
         row = {
@@ -176,9 +179,9 @@ def main():
     t_prep = 0.0
     if not mfma:
         def prep_loop():
-            for _ in range(copies):
+            for _ in range(loop_calls):
                 pb.pb_act_prep(d, Xd, 1, ws)
-        t_prep = timed(capture(prep_loop), reps) / copies
+        t_prep = timed(capture(prep_loop), reps) / loop_calls
 
     # ---- roofline of the dominant kernel over the sweep bits_used = 1..B (average launch) ----
     avg_kernel_s = kern_time_sum / B
@@ -247,6 +250,8 @@ def main():
         del pool, packed
         torch.cuda.empty_cache()
         out["batch_sweep"] = batch_sweep(torch, pb, synth, dev)
+    if not args.no_sizes:
+        out["size_sweep"] = size_sweep(torch, pb, dev, args.layout)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(W, X, B, layer_bytes)
 
@@ -268,6 +273,53 @@ def measured_traffic(kernel, n, B):
     except OSError:
         pass
     return None
+
+
+def size_sweep(torch, pb, dev, layout):
+    """Larger square layers (the north star's "4096 x 4096 +"): a 4096^2 bitlayer is 2 MiB, a fraction of a
+    microsecond of HBM time, so the per-call figures of the headline workload are latency-bound; these show the
+    bandwidth the same kernel reaches once a call streams tens of MiB.  Cold weights (copies rotated through
+    768 MiB), HIP-graph replay, batch 1.  Weights and activations ~N(0, 0.01) / N(0, 1) from the device generator."""
+    rows = []
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(200300822 + 6000)
+    lay = pb.PB_LAYOUT_TILE16_V1 if layout == "mfma" else pb.PB_LAYOUT_ROWMAJOR_V1
+    for n in (8192, 16384):
+        B = 8
+        Wd = torch.randn((n, n), device=dev, generator=gen) * 0.01
+        lin = pb.PackedLinear(Wd, B, layout=lay)
+        del Wd
+        X = torch.randn((1, n), device=dev, generator=gen)
+        Y = torch.empty((1, n), dtype=torch.float32, device=dev)
+        copies = max(3, POOL_BYTES // lin.packed.numel())
+        pool = [lin.packed] + [lin.packed.clone() for _ in range(copies - 1)]
+        layer_bytes = lin.packed.numel() // B
+        for m in (1, 4, 8):
+            def f():
+                for i in range(copies):
+                    pb.pb_matmul(pool[i], lin.scales, lin.desc, m, X, 1, Y, lin.workspace)
+            f()
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                f()
+            reps = max(3, 96 // copies)
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            g.replay()
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                g.replay()
+            e1.record()
+            torch.cuda.synchronize()
+            t = e0.elapsed_time(e1) * 1e-3 / (reps * copies)
+            rows.append({"size": n, "bits_used": m, "us_per_call": round(t * 1e6, 2),
+                         "eff_weight_GBps": round(layer_bytes * m / t / 1e9, 1),
+                         "hbm_frac": round(layer_bytes * m / t / 1e9 / HBM_PEAK_GBS, 4)})
+        del pool, lin
+        torch.cuda.empty_cache()
+    return {"workload": "FC n x n, B=8, batch 1, cold weights, whole call (one launch)", "rows": rows}
 
 
 def batch_sweep(torch, pb, synth, dev):
@@ -333,7 +385,7 @@ def cpu_baseline(W, X, B, layer_bytes):
         t0 = time.perf_counter()
         sweep(pool)
         one = time.perf_counter() - t0
-        reps = int(min(20, max(1, 10.0 / max(one, 1e-3))))
+        reps = int(min(1000, max(1, 12.0 / max(one, 1e-3))))    # about 12 s of host time
         t0 = time.perf_counter()
         for _ in range(reps):
             sweep(pool)
