@@ -57,6 +57,11 @@ typedef enum pb_status {
  *                       literally), kept as the measured alternative and for cols up to PB_MAX_COLS. */
 #define PB_LAYOUT_ROWMAJOR_V1 0x50420001u
 #define PB_LAYOUT_TILE16_V1 0x50420002u
+/* PB_LAYOUT_TILE16_GATES_V1  the tiled layout for the fused gate matrix of an LSTM (rows = 4H, gate order
+ *                       i, f, g, o): the four gate rows of a hidden unit share a row tile, so that
+ *                       pb_lstm_cell runs as ONE launch.  Every other call works on it too and sees the
+ *                       rows in their matrix order.  Chosen by the caller (pb_desc_init_layout). */
+#define PB_LAYOUT_TILE16_GATES_V1 0x50420003u
 
 /* Shape and format of one packed weight matrix (host struct, plain data).
  * bits      B, the number of stored bitlayers = two's-complement width of the
@@ -126,6 +131,14 @@ int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);
 int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X, int batch,
               float *Y, void *workspace, void *stream);
 
+/* pb_matmul with the layer's bias and nonlinearity applied before the store (the paper replaces each linear
+ * layer and keeps the nonlinearities in fp32, Sections 4.2-4.3):
+ *   Y[n][r] = act( fp32(sum_i scales[i] * A_i[r] * 2^-f) + bias[r] ),  act = identity or max(., 0).
+ *   bias  [rows] fp32 or NULL (read only);  act  a pb_activation. */
+typedef enum pb_activation { PB_ACT_NONE = 0, PB_ACT_RELU = 1 } pb_activation;
+int pb_matmul_bias_act(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X,
+                       int batch, const float *bias, int act, float *Y, void *workspace, void *stream);
+
 /* Same product, but returns the exact integer accumulators instead of Y:
  * A[i][n][r] = sum_c bit_i[r][c] * x_q[n][c], int64, for i < bits_used.
  * A: [bits_used][batch][rows], written. */
@@ -157,7 +170,10 @@ int pb_fixed_point(const pb_desc *d, const float *X, int batch, int32_t *xq, voi
  *   h' = sigmoid(g_o) tanh(c').
  *   x_t [batch][I], h_prev, c_prev [batch][H], bias [4H] or NULL: read only
  *   h_out, c_out [batch][H]: written (may alias h_prev / c_prev)
- *   input_size = I; H = d->rows / 4; d->cols must equal I + H. */
+ *   input_size = I; H = d->rows / 4; d->cols must equal I + H.
+ * With PB_LAYOUT_TILE16_GATES_V1 the product and the cell update are one launch, unless h_out overlaps
+ * h_prev (every workgroup reads all of h_prev, so an in-place update has to wait for the whole product:
+ * it then runs as two launches, like the other layouts). */
 int pb_lstm_cell(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *x_t,
                  int input_size, const float *h_prev, const float *c_prev, const float *bias, float *h_out,
                  float *c_out, int batch, void *workspace, void *stream);

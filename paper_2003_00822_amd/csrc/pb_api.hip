@@ -19,7 +19,8 @@ int check_desc(const pb_desc *d, pb::Layout *L)
     if (d->rows < 1 || d->cols < 1 || d->bits < 1 || d->bits > PB_MAX_BITS) return PB_EINVAL;
     if (d->frac_bits < 0 || d->frac_bits > 30) return PB_EINVAL;
     if (d->act_bits < 2 || d->act_bits > 32) return PB_EINVAL;
-    if (d->layout != PB_LAYOUT_ROWMAJOR_V1 && d->layout != PB_LAYOUT_TILE16_V1) return PB_EINVAL;
+    if (d->layout != PB_LAYOUT_ROWMAJOR_V1 && !pb::is_tile16(d->layout)) return PB_EINVAL;
+    if (d->layout == PB_LAYOUT_TILE16_GATES_V1 && d->rows % 4 != 0) return PB_EINVAL;
     if (d->cols > PB_MAX_COLS) return PB_ESIZE;
     if (!pb::make_layout(d->layout, d->rows, d->cols, d->bits, L)) return PB_ESIZE;
     if (pb::packed_bytes(*L) > 0xFFFFFFFFull) return PB_ESIZE;  // tiles are addressed with 32-bit byte offsets
@@ -103,7 +104,7 @@ int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream)
 
 static int matmul_common(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X0,
                          int cols0, const float *X1, int cols1, int batch, float *Y, int64_t *A, void *workspace,
-                         void *stream)
+                         void *stream, const pb::Epilogue &ep = pb::Epilogue())
 {
     pb::Layout L;
     int rc = check_desc(d, &L);
@@ -116,10 +117,11 @@ static int matmul_common(const void *packed, const float *scales, const pb_desc 
         (A && !aligned16(A)) || (scales && !aligned16(scales)) || (X1 && !aligned16(X1)))
         return PB_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (L.layout == PB_LAYOUT_TILE16_V1)   // conversion, bit transpose and product in one launch
+    if (ep.bias && !aligned16(ep.bias)) return PB_EALIGN;
+    if (pb::is_tile16(L.layout))   // conversion, bit transpose, product and epilogue in one launch
         return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                           d->act_bits, X0, cols0, X1, cols1, nullptr, batch, Y,
-                                          reinterpret_cast<long long *>(A), st));
+                                          reinterpret_cast<long long *>(A), ep, st));
     char *ws = static_cast<char *>(workspace);
     int *meta = reinterpret_cast<int *>(ws + pb::ws_meta_off(L, batch));
     uint32_t *planes = reinterpret_cast<uint32_t *>(ws + pb::ws_planes_off(L, batch));
@@ -127,6 +129,7 @@ static int matmul_common(const void *packed, const float *scales, const pb_desc 
     if (err) return hip_status(err);
     err = pb::launch_matvec(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits, planes, meta,
                             batch, Y, reinterpret_cast<long long *>(A), st);
+    if (!err && Y && (ep.bias || ep.relu)) err = pb::launch_bias_act(Y, ep.bias, ep.relu, L.rows, batch, st);
     return hip_status(err);
 }
 
@@ -135,6 +138,18 @@ int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bit
 {
     if (!Y || !d) return PB_EINVAL;
     return matmul_common(packed, scales, d, bits_used, X, d->cols, nullptr, 0, batch, Y, nullptr, workspace, stream);
+}
+
+int pb_matmul_bias_act(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X,
+                       int batch, const float *bias, int act, float *Y, void *workspace, void *stream)
+{
+    if (!Y || !d) return PB_EINVAL;
+    if (act != PB_ACT_NONE && act != PB_ACT_RELU) return PB_EINVAL;
+    pb::Epilogue ep;
+    ep.bias = bias;
+    ep.relu = act == PB_ACT_RELU;
+    return matmul_common(packed, scales, d, bits_used, X, d->cols, nullptr, 0, batch, Y, nullptr, workspace, stream,
+                         ep);
 }
 
 int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
@@ -174,10 +189,10 @@ int pb_matmul_prepared(const void *packed, const float *scales, const pb_desc *d
     char *ws = static_cast<char *>(workspace);
     const int *meta = reinterpret_cast<const int *>(ws + pb::ws_meta_off(L, batch));
     const uint32_t *planes = reinterpret_cast<const uint32_t *>(ws + pb::ws_planes_off(L, batch));
-    if (L.layout == PB_LAYOUT_TILE16_V1)
+    if (pb::is_tile16(L.layout))
         return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                           d->act_bits, nullptr, 0, nullptr, 0, planes, batch, Y, nullptr,
-                                          static_cast<hipStream_t>(stream)));
+                                          pb::Epilogue(), static_cast<hipStream_t>(stream)));
     return hip_status(pb::launch_matvec(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                         planes, meta, batch, Y, nullptr, static_cast<hipStream_t>(stream)));
 }
@@ -214,6 +229,24 @@ int pb_lstm_cell(const void *packed, const float *scales, const pb_desc *d, int 
     if (!aligned16(h_prev) || !aligned16(c_prev) || !aligned16(h_out) || !aligned16(c_out) ||
         (bias && !aligned16(bias)))
         return PB_EALIGN;
+    if (L.layout == PB_LAYOUT_TILE16_GATES_V1) {
+        // one launch, unless the new hidden state would overwrite the old one while other workgroups still read it
+        const size_t hbytes = (size_t)batch * (size_t)H * sizeof(float);
+        const char *ho = reinterpret_cast<const char *>(h_out), *hp = reinterpret_cast<const char *>(h_prev);
+        const char *xp = reinterpret_cast<const char *>(x_t);
+        const size_t xbytes = (size_t)batch * (size_t)input_size * sizeof(float);
+        const bool overlap = (ho < hp + hbytes && hp < ho + hbytes) || (ho < xp + xbytes && xp < ho + hbytes);
+        if (!overlap) {
+            pb::Epilogue ep;
+            ep.bias = bias;
+            ep.c_prev = c_prev;
+            ep.h_out = h_out;
+            ep.c_out = c_out;
+            // (Y is not written in this mode; matmul_common wants a non-null output)
+            return matmul_common(packed, scales, d, bits_used, x_t, input_size, h_prev, H, batch, h_out, nullptr,
+                                 workspace, stream, ep);
+        }
+    }
     float *gates = reinterpret_cast<float *>(static_cast<char *>(workspace) + pb::ws_gates_off(L, batch));
     rc = matmul_common(packed, scales, d, bits_used, x_t, input_size, h_prev, H, batch, gates, nullptr, workspace,
                        stream);

@@ -22,12 +22,26 @@ int launch_prep(const float *X0, int cols0, const float *X1, int cols1, int batc
 int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                   const uint32_t *planes, const int *meta, int batch, float *Y, long long *A, hipStream_t st);
 
-// pb_mfma.hip: the whole of Algorithm 2 in one launch on the matrix cores (PB_LAYOUT_TILE16_V1).  Activations come
+// pb_mfma.hip: the whole of Algorithm 2 in one launch on the matrix cores (the tiled layouts).  Activations come
 // from X0 / X1 (converted and bit-transposed inside the kernel) or, if `planes` is non-null, from bit planes that
 // launch_prep left in memory.  Exactly one of Y / A is non-null.
+// What follows the product in the same launch: bias and ReLU before the store of Y, or (PB_LAYOUT_TILE16_GATES_V1
+// only) the LSTM cell update, which writes h_out / c_out [batch][H] instead of Y.
+struct Epilogue {
+    const float *bias = nullptr;   // [rows] or null
+    int relu = 0;
+    const float *c_prev = nullptr; // non-null: fused LSTM cell
+    float *h_out = nullptr, *c_out = nullptr;
+};
 int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
-                int batch, float *Y, long long *A, hipStream_t st);
+                int batch, float *Y, long long *A, const Epilogue &ep, hipStream_t st);
+
+// logistic function of the LSTM gates (one definition for the fused and the stand-alone cell update)
+__device__ __forceinline__ float sigmoid_f(float v) { return 1.0f / (1.0f + expf(-v)); }
+
+// pb_lstm.hip: y = act(y + bias) in place, for the layout whose product kernel has no fused epilogue
+int launch_bias_act(float *Y, const float *bias, int relu, int rows, int batch, hipStream_t st);
 
 // pb_lstm.hip: gate nonlinearities and state update on the gate pre-activations.
 int launch_lstm_pointwise(const float *gates, const float *bias, const float *c_prev, int H, int batch, float *h_out,

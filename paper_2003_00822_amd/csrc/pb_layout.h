@@ -15,6 +15,12 @@
 //   the 16 bytes at l * 16, the words 16 * chunk + 4 * kb + t (t = 0..3) of row j.
 //   One 16-byte load per lane fetches a whole block, fully coalesced, and word t of
 //   every lane is the B operand of one 16x16x128 matrix instruction (row j, k-block kb).
+//
+// PB_LAYOUT_TILE16_GATES_V1: the same blocks for the fused gate matrix of an LSTM (rows = 4H
+//   in gate order i, f, g, o): row tile t holds the four gate rows of the hidden units 4t .. 4t+3,
+//   packed row 16 t + 4 (u % 4) + gate = matrix row gate * H + u.  All four pre-activations of
+//   a hidden unit then end in one row tile, so the cell update can follow the product in
+//   the same launch.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -49,7 +55,22 @@ struct Layout {
     // PB_LAYOUT_TILE16_V1
     int rt_count;  // row tiles: rows_p / 16
     int cq;        // chunks per row: cwp / 16
+    int gate_h;    // PB_LAYOUT_TILE16_GATES_V1: H = rows / 4 (rows are stored gate-interleaved), else 0
 };
+
+inline bool is_tile16(uint32_t layout) { return layout == PB_LAYOUT_TILE16_V1 || layout == PB_LAYOUT_TILE16_GATES_V1; }
+
+// PB_LAYOUT_TILE16_GATES_V1: packed row of matrix row r, and back (-1 = a padding row).
+__host__ __device__ inline int gates_packed_row(int r, int H)
+{
+    const int gate = r / H, u = r - gate * H;
+    return (u >> 2) * 16 + (u & 3) * 4 + gate;
+}
+__host__ __device__ inline int gates_matrix_row(int pr, int H)
+{
+    const int u = (pr >> 4) * 4 + ((pr >> 2) & 3), gate = pr & 3;
+    return u < H ? gate * H + u : -1;
+}
 
 inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L)
 {
@@ -58,7 +79,7 @@ inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L
     L->layout = layout;
     L->rows = rows; L->cols = cols; L->bits = bits;
     L->cw = (cols + 31) / 32;
-    L->ws = L->csplit = L->rpt = L->rt_count = L->cq = 0;
+    L->ws = L->csplit = L->rpt = L->rt_count = L->cq = L->gate_h = 0;
     if (layout == PB_LAYOUT_ROWMAJOR_V1) {
         int best_ws = 0, best_pad = 0;
         const int cand[3] = {128, 64, 32};
@@ -77,11 +98,17 @@ inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L
         L->cwp = best_pad;
         L->rpt = kTileWords / best_ws;
         L->rows_p = (rows + 3) & ~3;
-    } else if (layout == PB_LAYOUT_TILE16_V1) {
+    } else if (is_tile16(layout)) {
         if (cols > kMaxColsTile16) return false;
         L->cq = (L->cw + kChunkWords - 1) / kChunkWords;
         L->cwp = L->cq * kChunkWords;
-        L->rt_count = (rows + kTileRows - 1) / kTileRows;
+        if (layout == PB_LAYOUT_TILE16_GATES_V1) {
+            if (rows % 4 != 0) return false;
+            L->gate_h = rows / 4;
+            L->rt_count = (L->gate_h + 3) / 4;       // four hidden units (16 gate rows) per tile
+        } else {
+            L->rt_count = (rows + kTileRows - 1) / kTileRows;
+        }
         L->rows_p = L->rt_count * kTileRows;
     } else {
         return false;
@@ -95,7 +122,7 @@ inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L
 inline size_t tile16_layer_stride(const Layout &L) { return L.layer_words; }
 inline size_t tile16_rowtile_stride(const Layout &L) { return (size_t)L.cq * 256; }
 
-// Position (in words) of word w of row r of bitlayer `layer`.
+// Position (in words) of word w of PACKED row r of bitlayer `layer`.
 __host__ __device__ inline size_t word_index(uint32_t layout, int cwp, size_t layer_words, int layer, int r, int w)
 {
     if (layout == PB_LAYOUT_ROWMAJOR_V1) return (size_t)layer * layer_words + (size_t)r * (size_t)cwp + (size_t)w;

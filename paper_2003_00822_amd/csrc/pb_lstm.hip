@@ -9,8 +9,6 @@
 
 namespace pb {
 
-__device__ __forceinline__ float sigmoid_f(float v) { return 1.0f / (1.0f + expf(-v)); }
-
 __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict__ gates, const float *__restrict__ bias,
                                                         const float *__restrict__ c_prev, int H, int batch,
                                                         float *__restrict__ h_out, float *__restrict__ c_out)
@@ -25,6 +23,24 @@ __global__ __launch_bounds__(256) void k_lstm_pointwise(const float *__restrict_
     float hn = sigmoid_f(go) * tanhf(cn);
     c_out[idx] = cn;
     h_out[idx] = hn;
+}
+
+__global__ __launch_bounds__(256) void k_bias_act(float *__restrict__ Y, const float *__restrict__ bias, int relu,
+                                                  int rows, int total)
+{
+    int idx = blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= total) return;
+    float y = Y[idx];
+    if (bias) y += bias[idx % rows];
+    if (relu) y = fmaxf(y, 0.0f);
+    Y[idx] = y;
+}
+
+int launch_bias_act(float *Y, const float *bias, int relu, int rows, int batch, hipStream_t st)
+{
+    int total = rows * batch;
+    hipLaunchKernelGGL(k_bias_act, dim3((total + 255) / 256), dim3(256), 0, st, Y, bias, relu, rows, total);
+    return (int)hipGetLastError();
 }
 
 int launch_lstm_pointwise(const float *gates, const float *bias, const float *c_prev, int H, int batch, float *h_out,

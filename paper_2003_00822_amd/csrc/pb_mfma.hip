@@ -50,6 +50,11 @@ struct MfmaArgs {
     const float *scales;
     float *Y;
     long long *A;
+    const float *bias;          // [rows] or null: added to the fp32 result
+    const float *c_prev;        // non-null: LSTM cell update instead of the store of Y (gate-interleaved rows)
+    float *h_out, *c_out;
+    int relu;                   // max(., 0) before the store of Y
+    int gate_h;                 // gate-interleaved rows: H (packed row 16 t + 4 (u % 4) + gate = row gate * H + u), else 0
     size_t packed_bytes;
     uint32_t layer_step, round_step;   // bytes from one bitlayer of a row tile to the next, from one row tile to the next
     int cols0, cols1;
@@ -79,6 +84,13 @@ __device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
 }
 
 // value of lane (l ^ J) for J < 16, inside each row of 16 lanes, on the vector ALU alone (DPP modifiers)
+// value of lane Q of the caller's quad of lanes
+template <int Q>
+__device__ __forceinline__ float quad_bcast_f(float v)
+{
+    return __uint_as_float(dpp_mov<Q * 0x55>(__float_as_uint(v)));
+}
+
 template <int J>
 __device__ __forceinline__ uint32_t row_xor(uint32_t v)
 {
@@ -269,7 +281,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                             __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
         }
         if (a.X1) {
-            // second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range
+            // Second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range.
+            // Columns of the first part would have negative offsets here; those are clamped and the value dropped
+            // (a negative register offset that an instruction offset brings back above zero is not range-checked
+            // lane by lane on this hardware).
             const int colb1 = colb - a.cols0 * 4;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
@@ -282,9 +297,11 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
 #pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            xv[v][q][t][e] |=
-                                __builtin_amdgcn_raw_buffer_load_b32(rx1, colb1 + 128 * (16 * q + 4 * e + t), 0, 0);
+                        for (int e = 0; e < 2; ++e) {
+                            const int off = colb1 + 128 * (16 * q + 4 * e + t);
+                            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rx1, max(off, 0), 0, 0);
+                            xv[v][q][t][e] |= off >= 0 ? w : 0u;
+                        }
             }
         }
         __builtin_amdgcn_sched_barrier(0x7);
@@ -368,8 +385,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     __syncthreads();
                     if (wave == pr % nwaves) {
                         const int g = lane >> 4, v = g % NV, n = n0 + v;
-                        const int row = (rt0 + pr) * kTileRows + j;
-                        const bool live = n < a.batch && row < a.R;
+                        const int prow = (rt0 + pr) * kTileRows + j;
+                        const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
+                        const bool live = n < a.batch && row >= 0 && row < a.R;
                         double z = 0.0;
                         for (int i = g / NV; i < m; i += LS) {
                             int2 *src = &abuf[pr & 1][v][i][j];
@@ -387,7 +405,22 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         if (!a.A) {
                             if (LS >= 2) z += __shfl_xor(z, 16 * NV, 64);
                             if (LS >= 4) z += __shfl_xor(z, 32, 64);
-                            if (live && g < NV) a.Y[(size_t)n * a.R + row] = (float)(z * a.out_scale);
+                            float y = (float)(z * a.out_scale);
+                            if (a.bias && live) y += a.bias[row];
+                            if (a.c_prev) {
+                                // LSTM cell: the quad of lanes 4 u' .. 4 u' + 3 holds the gates i, f, g, o of one unit
+                                const float gi = quad_bcast_f<0>(y), gf = quad_bcast_f<1>(y);
+                                const float gg = quad_bcast_f<2>(y), go = quad_bcast_f<3>(y);
+                                if (live && g < NV && (j & 3) == 0) {
+                                    const size_t at = (size_t)n * a.gate_h + (size_t)row;   // gate 0: row = unit
+                                    const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
+                                    a.c_out[at] = cn;
+                                    a.h_out[at] = sigmoid_f(go) * tanhf(cn);
+                                }
+                            } else {
+                                if (a.relu) y = fmaxf(y, 0.0f);
+                                if (live && g < NV) a.Y[(size_t)n * a.R + row] = y;
+                            }
                         }
                     }
                     ++pr;
@@ -468,10 +501,12 @@ static int resident_workgroups(int variant, int S)
 
 int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
-                int batch, float *Y, long long *A, hipStream_t st)
+                int batch, float *Y, long long *A, const Epilogue &ep, hipStream_t st)
 {
     MfmaArgs a;
     a.packed = packed; a.X0 = X0; a.X1 = X1; a.planes = planes; a.scales = scales; a.Y = Y; a.A = A;
+    a.bias = ep.bias; a.relu = ep.relu; a.c_prev = ep.c_prev; a.h_out = ep.h_out; a.c_out = ep.c_out;
+    a.gate_h = L.gate_h;
     a.packed_bytes = packed_bytes(L);
     a.layer_step = (uint32_t)(tile16_layer_stride(L) * 4);
     a.round_step = (uint32_t)(tile16_rowtile_stride(L) * 4);

@@ -55,18 +55,19 @@ __device__ __forceinline__ int quantize_code(float w, float d, int bits)
 
 // one thread per (padded row, padded word): builds that word of every bitlayer
 __global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint32_t layout, int rows, int cols,
-                                              int bits, int cw, int cwp, int rows_p, size_t layer_words,
+                                              int bits, int cw, int cwp, int rows_p, int gate_h, size_t layer_words,
                                               const uint32_t *__restrict__ absmax_slot, uint32_t *__restrict__ packed)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     size_t total = (size_t)rows_p * (size_t)cwp;
     if (idx >= total) return;
-    int r = (int)(idx / (size_t)cwp);
+    const int pr = (int)(idx / (size_t)cwp);       // packed row
     int w = (int)(idx % (size_t)cwp);
+    const int r = gate_h ? gates_matrix_row(pr, gate_h) : pr;   // matrix row (-1 or >= rows: padding)
     uint32_t wd[PB_MAX_BITS];
 #pragma unroll
     for (int i = 0; i < PB_MAX_BITS; ++i) wd[i] = 0;
-    if (r < rows && w < cw) {
+    if (r >= 0 && r < rows && w < cw) {
         float d = grid_step(__uint_as_float(*absmax_slot), bits);
         const float *src = W + (size_t)r * (size_t)cols;
         for (int b = 0; b < 32; ++b) {
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint3
     }
 #pragma unroll
     for (int i = 0; i < PB_MAX_BITS; ++i)
-        if (i < bits) packed[word_index(layout, cwp, layer_words, i, r, w)] = wd[i];
+        if (i < bits) packed[word_index(layout, cwp, layer_words, i, pr, w)] = wd[i];
 }
 
 // reads max|W| from scales[0] (where k_absmax left it) and writes the layer scales
@@ -95,15 +96,17 @@ __global__ void k_scales(float *scales, int bits)
 }
 
 __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ packed, uint32_t layout, int rows, int cols,
-                                                int bits, int cwp, size_t layer_words, int32_t *__restrict__ q)
+                                                int bits, int cwp, int gate_h, size_t layer_words,
+                                                int32_t *__restrict__ q)
 {
     size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= (size_t)rows * (size_t)cols) return;
     int r = (int)(idx / (size_t)cols);
     int c = (int)(idx % (size_t)cols);
     uint32_t u = 0;
+    const int pr = gate_h ? gates_packed_row(r, gate_h) : r;
     for (int i = 0; i < bits; ++i) {
-        uint32_t word = packed[word_index(layout, cwp, layer_words, i, r, c >> 5)];
+        uint32_t word = packed[word_index(layout, cwp, layer_words, i, pr, c >> 5)];
         u |= ((word >> (c & 31)) & 1u) << (bits - 1 - i);
     }
     int32_t v = (int32_t)(u << (32 - bits)) >> (32 - bits);  // sign-extend the B-bit code
@@ -121,7 +124,7 @@ int launch_quantize_pack(const float *W, const Layout &L, uint32_t *packed, floa
     hipLaunchKernelGGL(k_absmax, dim3(blocks), dim3(256), 0, st, W, n, slot);
     size_t total = L.layer_words;
     hipLaunchKernelGGL(k_pack, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, L.layout, L.rows, L.cols,
-                       L.bits, L.cw, L.cwp, L.rows_p, L.layer_words, slot, packed);
+                       L.bits, L.cw, L.cwp, L.rows_p, L.gate_h, L.layer_words, slot, packed);
     hipLaunchKernelGGL(k_scales, dim3(1), dim3(64), 0, st, scales, L.bits);
     return (int)hipGetLastError();
 }
@@ -130,7 +133,7 @@ int launch_unpack(const uint32_t *packed, const Layout &L, int32_t *q, hipStream
 {
     size_t n = (size_t)L.rows * (size_t)L.cols;
     hipLaunchKernelGGL(k_unpack, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, packed, L.layout, L.rows, L.cols,
-                       L.bits, L.cwp, L.layer_words, q);
+                       L.bits, L.cwp, L.gate_h, L.layer_words, q);
     return (int)hipGetLastError();
 }
 

@@ -21,10 +21,12 @@ PB_MAX_COLS = 32768
 PB_MAX_BATCH = 4096
 PB_LAYOUT_ROWMAJOR_V1 = 0x50420001   # AND + popcount kernel
 PB_LAYOUT_TILE16_V1 = 0x50420002     # matrix-core kernel (the default up to 16384 columns)
+PB_LAYOUT_TILE16_GATES_V1 = 0x50420003   # the same with the four gate rows of an LSTM unit in one row tile
+PB_ACT_NONE, PB_ACT_RELU = 0, 1
 
 EXPORTS = [
     "pb_desc_init", "pb_desc_init_layout", "pb_quantize_pack_desc", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
-    "pb_matmul_acc", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
+    "pb_matmul_bias_act", "pb_matmul_acc", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
 ]
 
 
@@ -70,6 +72,8 @@ def lib():
         L.pb_unpack.restype = _I
         L.pb_matmul.argtypes = [_P, _P, _D, _I, _P, _I, _P, _P, _P]
         L.pb_matmul.restype = _I
+        L.pb_matmul_bias_act.argtypes = [_P, _P, _D, _I, _P, _I, _P, _I, _P, _P, _P]
+        L.pb_matmul_bias_act.restype = _I
         L.pb_matmul_acc.argtypes = [_P, _D, _I, _P, _I, _P, _P, _P]
         L.pb_matmul_acc.restype = _I
         L.pb_act_prep.argtypes = [_D, _P, _I, _P, _P]
@@ -171,6 +175,14 @@ def pb_matmul(packed, scales, d, bits_used, X, batch, Y, workspace, stream=None)
                            ctypes.byref(d), bits_used, _ptr(X, torch.float32, "X"), batch,
                            _ptr(Y, torch.float32, "Y"), _ptr(workspace, torch.uint8, "workspace"),
                            _stream(stream)), "pb_matmul")
+
+
+def pb_matmul_bias_act(packed, scales, d, bits_used, X, batch, bias, act, Y, workspace, stream=None):
+    _check(lib().pb_matmul_bias_act(_ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float32, "scales"),
+                                    ctypes.byref(d), bits_used, _ptr(X, torch.float32, "X"), batch,
+                                    _ptr(bias, torch.float32, "bias"), act, _ptr(Y, torch.float32, "Y"),
+                                    _ptr(workspace, torch.uint8, "workspace"), _stream(stream)),
+           "pb_matmul_bias_act")
 
 
 def pb_matmul_acc(packed, d, bits_used, X, batch, A, workspace, stream=None):

@@ -213,6 +213,69 @@ def test_extra_16384(pb, layout):
         assert_y_close(Y_gpu[:, r], y, sub[:, 0, :], prep["scales"])
 
 
+GATES = 0x50420003
+
+
+@pytest.mark.parametrize("H,I,batch", [(5, 3, 1), (37, 100, 2), (64, 64, 4), (1500, 1500, 1)])
+def test_gate_interleaved_layout_is_transparent(pb, H, I, batch):
+    """The LSTM layout stores rows gate-interleaved; codes, accumulators and outputs come back in matrix order."""
+    W, X = synth.ragged(4 * H, I + H, batch=batch, case=13, xdist="uniform")
+    print("gates layout", H, I, batch, flush=True)
+    run_layer(pb, W, 4, X, [1, 3, 4], layout=GATES)
+
+
+def test_gate_layout_needs_rows_multiple_of_4(pb):
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_desc_init_layout(10, 64, 4, GATES)
+    assert e.value.status in (pb.PB_EINVAL, pb.PB_ESIZE)
+
+
+@pytest.mark.parametrize("lay", ["mfma", "popc"])
+@pytest.mark.parametrize("act", [0, 1])
+def test_bias_and_relu_epilogue(pb, lay, act):
+    W, X = synth.ragged(123, 900, batch=3, case=17, xdist="normal")
+    bits, m = 5, 4
+    rng = np.random.default_rng(17)
+    bias = rng.normal(size=123).astype(np.float32)
+    lin = pb.PackedLinear(dev(W), bits, max_batch=3, layout=LAYOUTS[lay])
+    ref = oracle_reference(W, bits, X, m)
+    want = ref["Y"] + bias[None, :]                      # fp32 add, as in the kernel
+    if act:
+        want = np.maximum(want, np.float32(0))
+    Y = torch.empty((3, 123), dtype=torch.float32, device="cuda")
+    pb.pb_matmul_bias_act(lin.packed, lin.scales, lin.desc, m, dev(X), 3, dev(bias), act, Y, lin.workspace)
+    got = Y.cpu().numpy()
+    tol = 1e-5 * np.abs(ref["Y"]) + 1e-6 * np.abs(bias[None, :]) + 1e-30
+    assert (np.abs(got - want) <= tol).all()
+    # without bias
+    pb.pb_matmul_bias_act(lin.packed, lin.scales, lin.desc, m, dev(X), 3, None, act, Y, lin.workspace)
+    want = np.maximum(ref["Y"], np.float32(0)) if act else ref["Y"]
+    assert_y_close(Y.cpu().numpy(), want, ref["A"], ref["scales"])
+
+
+def test_lstm_fused_cell_small_ragged(pb):
+    """Fused product + cell update (one launch) on shapes whose H is not a multiple of 4 and with a batch."""
+    for (H, I, N) in [(5, 7, 1), (38, 50, 3), (130, 70, 2), (37, 33, 1), (21, 1001, 2), (300, 2, 1)]:
+        W, X = synth.ragged(4 * H, I + H, batch=N, case=19, xdist="uniform")
+        rng = np.random.default_rng(19)
+        bias = rng.normal(size=4 * H).astype(np.float32) * 0.1
+        c0 = rng.normal(size=(N, H)).astype(np.float32)
+        x_t, h0 = X[:, :I].copy(), X[:, I:].copy()
+        bits, m = 5, 5
+        prep = po.prepare(W, bits)
+        lw = po.pack_words(prep["layers"])
+        _, Y_or = po.matmul_words(lw, prep["scales"], m, I + H, X)
+        h_ref, c_ref = po.lstm_pointwise(Y_or, bias, c0)
+        lin = pb.PackedLinear(dev(W), bits, max_batch=N, layout=GATES)
+        h_out = torch.empty((N, H), device="cuda")
+        c_out = torch.empty((N, H), device="cuda")
+        pb.pb_lstm_cell(lin.packed, lin.scales, lin.desc, m, dev(x_t), I, dev(h0), dev(c0), dev(bias), h_out, c_out,
+                        N, lin.workspace)
+        assert np.abs(h_out.cpu().numpy() - h_ref).max() < 2e-6, (H, I, N)
+        assert np.abs(c_out.cpu().numpy() - c_ref).max() < 2e-6, (H, I, N)
+
+
+@pytest.mark.parametrize("layout", [LAYOUTS["mfma"], LAYOUTS["popc"], GATES], ids=["mfma", "popc", "gates"])
 def test_lstm_cell_config4(pb, layout):
     """Config 4: 35 sequential LSTM steps.  Integer parity is checked per step with oracle-fed state
     (teacher forcing); the free-running GPU recurrence is compared to a tolerance."""
@@ -228,6 +291,8 @@ def test_lstm_cell_config4(pb, layout):
     c_or = np.zeros((1, H), dtype=np.float32)
     h_free = torch.zeros((1, H), device="cuda")
     c_free = torch.zeros((1, H), device="cuda")
+    h_pp = [torch.zeros((1, H), device="cuda"), torch.zeros((1, H), device="cuda")]   # ping-pong (never aliased)
+    c_pp = torch.zeros((1, H), device="cuda")
     for t in range(35):
         xin = np.concatenate([xs[t], h_or], axis=1)
         A_or, Y_or = po.matmul_words(lw, prep["scales"], m, I + H, xin)
@@ -244,9 +309,12 @@ def test_lstm_cell_config4(pb, layout):
         assert np.abs(c_out.cpu().numpy() - c_new).max() < 2e-6, "step %d" % t
         # free-running GPU recurrence (in place)
         pb.pb_lstm_cell(packed, scales, d, m, dev(xs[t]), I, h_free, c_free, bias_d, h_free, c_free, 1, ws)
+        pb.pb_lstm_cell(packed, scales, d, m, dev(xs[t]), I, h_pp[t & 1], c_pp, bias_d, h_pp[(t + 1) & 1], c_pp, 1, ws)
         h_or, c_or = h_new, c_new
     assert np.abs(h_free.cpu().numpy() - h_or).max() < 1e-4
     assert np.abs(c_free.cpu().numpy() - c_or).max() < 1e-4
+    assert np.abs(h_pp[35 & 1].cpu().numpy() - h_or).max() < 1e-4
+    assert np.abs(c_pp.cpu().numpy() - c_or).max() < 1e-4
 
 
 def test_errors_surface_as_status(pb):
