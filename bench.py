@@ -46,6 +46,7 @@ def parse():
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--no-batch", action="store_true", help="skip the batched (8192 x 8192, batch 1..64) comparison")
     ap.add_argument("--no-sizes", action="store_true", help="skip the larger layers (8192, 16384: bandwidth asymptote)")
+    ap.add_argument("--no-models", action="store_true", help="skip the MLP forward and the 35-step LSTM sequence")
     ap.add_argument("--calib", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
@@ -252,6 +253,8 @@ def main():
         out["batch_sweep"] = batch_sweep(torch, pb, synth, dev)
     if not args.no_sizes:
         out["size_sweep"] = size_sweep(torch, pb, dev, args.layout)
+    if not args.no_models:
+        out["models"] = model_sequences(torch, pb, synth, dev)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(W, X, B, layer_bytes)
 
@@ -273,6 +276,72 @@ def measured_traffic(kernel, n, B):
     except OSError:
         pass
     return None
+
+
+def model_sequences(torch, pb, synth, dev):
+    """The layer sequences of the paper's models on the matrix-core kernel, each captured in one HIP graph:
+    the 3-layer MLP 784-4096-4096-10 (one launch per layer, bias-free, ReLU fused into the store) and 35
+    sequential steps of the LSTM cell (hidden = input = 1500, fused gate matrix 6000 x 3000, one launch per step:
+    product and cell update together, hidden state ping-ponged between two buffers).  Batch 1, weights warm
+    (a model's own weights, a few MiB, are what stays in cache between its steps)."""
+    res = {}
+    # ---- MLP
+    Ws, X = synth.mlp()
+    B = 8
+    lins = [pb.PackedLinear(torch.from_numpy(W).to(dev), B) for W in Ws]
+    acts = [torch.from_numpy(X).to(dev)] + [torch.empty((1, W.shape[0]), dtype=torch.float32, device=dev) for W in Ws]
+    rows = []
+    for m in (2, 4, 8):
+        def fwd():
+            for li, lin in enumerate(lins):
+                pb.pb_matmul_bias_act(lin.packed, lin.scales, lin.desc, m, acts[li], 1, None,
+                                      pb.PB_ACT_RELU if li < 2 else pb.PB_ACT_NONE, acts[li + 1], lin.workspace)
+        rows.append({"bits_used": m, "us_per_forward": round(_graph_time(torch, fwd, 32) * 1e6, 2)})
+    res["mlp_784_4096_4096_10"] = {"launches_per_forward": 3, "weight_bits_stored": B, "rows": rows}
+    del lins
+    # ---- LSTM
+    H = I = 1500
+    W, xs, bias = synth.lstm(H, I, steps=35)
+    rows = []
+    xs_d = [torch.from_numpy(x).to(dev) for x in xs]
+    bias_d = torch.from_numpy(bias).to(dev)
+    for B in (4, 8):
+        lin = pb.PackedLinear(torch.from_numpy(W).to(dev), B, layout=pb.PB_LAYOUT_TILE16_GATES_V1)
+        h = [torch.zeros((1, H), device=dev), torch.zeros((1, H), device=dev)]
+        c = torch.zeros((1, H), device=dev)
+        for m in sorted({2, B}):
+            def seq():
+                for t in range(35):
+                    pb.pb_lstm_cell(lin.packed, lin.scales, lin.desc, m, xs_d[t], I, h[t & 1], c, bias_d,
+                                    h[(t + 1) & 1], c, 1, lin.workspace)
+            t35 = _graph_time(torch, seq, 1)
+            rows.append({"weight_bits_stored": B, "bits_used": m, "us_per_step": round(t35 * 1e6 / 35, 2),
+                         "us_per_35_steps": round(t35 * 1e6, 1)})
+        del lin
+    res["lstm_1500_35_steps"] = {"launches_per_step": 1, "rows": rows}
+    return res
+
+
+def _graph_time(torch, fn, per_graph):
+    """Seconds per call of fn, captured `per_graph` times into one HIP graph and replayed."""
+    def body():
+        for _ in range(per_graph):
+            fn()
+    body()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        body()
+    g.replay()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(20):
+        g.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) * 1e-3 / (20 * per_graph)
 
 
 def size_sweep(torch, pb, dev, layout):
