@@ -363,16 +363,17 @@ def size_sweep(torch, pb, dev, layout):
         copies = max(3, POOL_BYTES // lin.packed.numel())
         pool = [lin.packed] + [lin.packed.clone() for _ in range(copies - 1)]
         layer_bytes = lin.packed.numel() // B
+        calls = max(copies, 24)      # per captured graph (a graph launch costs several microseconds itself)
         for m in (1, 4, 8):
             def f():
-                for i in range(copies):
-                    pb.pb_matmul(pool[i], lin.scales, lin.desc, m, X, 1, Y, lin.workspace)
+                for i in range(calls):
+                    pb.pb_matmul(pool[i % copies], lin.scales, lin.desc, m, X, 1, Y, lin.workspace)
             f()
             torch.cuda.synchronize()
             g = torch.cuda.CUDAGraph()
             with torch.cuda.graph(g):
                 f()
-            reps = max(3, 96 // copies)
+            reps = max(3, 96 // calls)
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             g.replay()
@@ -382,7 +383,7 @@ def size_sweep(torch, pb, dev, layout):
                 g.replay()
             e1.record()
             torch.cuda.synchronize()
-            t = e0.elapsed_time(e1) * 1e-3 / (reps * copies)
+            t = e0.elapsed_time(e1) * 1e-3 / (reps * calls)
             rows.append({"size": n, "bits_used": m, "us_per_call": round(t * 1e6, 2),
                          "eff_weight_GBps": round(layer_bytes * m / t / 1e9, 1),
                          "hbm_frac": round(layer_bytes * m / t / 1e9 / HBM_PEAK_GBS, 4)})

@@ -84,11 +84,11 @@ __device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
 }
 
 // value of lane (l ^ J) for J < 16, inside each row of 16 lanes, on the vector ALU alone (DPP modifiers)
-// value of lane Q of the caller's quad of lanes
-template <int Q>
-__device__ __forceinline__ float quad_bcast_f(float v)
+// value of lane L of the wave (a scalar)
+template <int L>
+__device__ __forceinline__ float lane_value(float v)
 {
-    return __uint_as_float(dpp_mov<Q * 0x55>(__float_as_uint(v)));
+    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), L));
 }
 
 template <int J>
@@ -98,6 +98,20 @@ __device__ __forceinline__ uint32_t row_xor(uint32_t v)
     else if constexpr (J == 4) return dpp_mov<0x1B>(dpp_mov<0x141>(v)); // row_half_mirror (l ^ 7), then quad_perm [3,2,1,0] (l ^ 3)
     else if constexpr (J == 2) return dpp_mov<0x4E>(v);                 // quad_perm [2,3,0,1]
     else return dpp_mov<0xB1>(v);                                       // quad_perm [1,0,3,2]
+}
+
+// sum over the 16 lanes of a row, in every lane (xor butterfly on the vector ALU)
+__device__ __forceinline__ double row_sum16(double z)
+{
+#define PB_STEP(J)                                                                                  \
+    {                                                                                               \
+        const unsigned long long b = (unsigned long long)__double_as_longlong(z);                   \
+        const uint32_t lo = row_xor<J>((uint32_t)b), hi = row_xor<J>((uint32_t)(b >> 32));          \
+        z += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));                \
+    }
+    PB_STEP(8) PB_STEP(4) PB_STEP(2) PB_STEP(1)
+#undef PB_STEP
+    return z;
 }
 
 // Per-lane constants of the 16 x 16 bit-matrix transpose across a row of 16 lanes (both 16-bit halves of a
@@ -179,7 +193,6 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     // them: a small head start keeps HBM busy during the transpose, the rest of the ring follows once the planes
     // are built.
     constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
-    constexpr int LS = 4 / NV;   // lanes (groups of 16) that share the bitlayers of one vector in the final sum
     // (low 16 planes, high 16 planes) sums per vector, bitlayer and row; two buffers, used by alternate row tiles
     __shared__ int2 abuf[2][NV][PB_MAX_BITS][kTileRows];
     __shared__ float s_scales[PB_MAX_BITS];
@@ -376,51 +389,50 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     atomicAdd(&dst->y, (int)hi_f);
                 }
                 if (++pi == m) {
-                    // The row tile is complete in every slice: one wave (taking turns) scales and stores it.
-                    // (The barrier per row tile also keeps the waves of a workgroup on one contiguous region of
-                    // the weight stream; letting them drift apart over several row tiles measured 5-15 % slower.)
-                    // Lane = (group g of 16, row j); group g works on vector g % NV and on the bitlayers
-                    // g / NV, g / NV + LS, ...; the LS partial sums of a vector are then added across groups.
+                    // The row tile is complete in every slice: scale and store it.  (The barrier per row tile also
+                    // keeps the waves of a workgroup on one contiguous region of the weight stream; letting them
+                    // drift apart over several row tiles measured 5-15 % slower.)
+                    // A task = (vector, four rows); lane = (row of the four, bitlayer): every lane converts one
+                    // (row, bitlayer) sum, the 16 lanes of a row add up their scaled terms.  The waves share the
+                    // 4 * NV tasks out, so that none of them is late for the next barrier.
                     pi = 0;
                     __syncthreads();
-                    if (wave == pr % nwaves) {
-                        const int g = lane >> 4, v = g % NV, n = n0 + v;
-                        const int prow = (rt0 + pr) * kTileRows + j;
+                    const int rq = lane >> 4, il = lane & 15;
+                    for (int task = wave; task < 4 * NV; task += nwaves) {
+                        const int v = task >> 2, jrow = (task & 3) * 4 + rq, n = n0 + v;
+                        const int prow = (rt0 + pr) * kTileRows + jrow;
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
                         const bool live = n < a.batch && row >= 0 && row < a.R;
-                        double z = 0.0;
-                        for (int i = g / NV; i < m; i += LS) {
-                            int2 *src = &abuf[pr & 1][v][i][j];
-                            const int2 s = *src;
+                        int2 s = make_int2(0, 0);
+                        if (il < m) {
+                            int2 *src = &abuf[pr & 1][v][il][jrow];
+                            s = *src;
                             *src = make_int2(0, 0);
-                            // A_i = lo + hi * 2^16 exactly: lo < 2^31 (unsigned), |hi| <= 2^30
-                            if (a.A) {
-                                if (live)
-                                    a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
-                                        (long long)(uint32_t)s.x + ((long long)s.y << 16);
-                            } else {
-                                z += (double)s_scales[i] * ((double)(uint32_t)s.x + (double)s.y * 65536.0);
-                            }
                         }
-                        if (!a.A) {
-                            if (LS >= 2) z += __shfl_xor(z, 16 * NV, 64);
-                            if (LS >= 4) z += __shfl_xor(z, 32, 64);
-                            float y = (float)(z * a.out_scale);
-                            if (a.bias && live) y += a.bias[row];
-                            if (a.c_prev) {
-                                // LSTM cell: the quad of lanes 4 u' .. 4 u' + 3 holds the gates i, f, g, o of one unit
-                                const float gi = quad_bcast_f<0>(y), gf = quad_bcast_f<1>(y);
-                                const float gg = quad_bcast_f<2>(y), go = quad_bcast_f<3>(y);
-                                if (live && g < NV && (j & 3) == 0) {
-                                    const size_t at = (size_t)n * a.gate_h + (size_t)row;   // gate 0: row = unit
-                                    const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
-                                    a.c_out[at] = cn;
-                                    a.h_out[at] = sigmoid_f(go) * tanhf(cn);
-                                }
-                            } else {
-                                if (a.relu) y = fmaxf(y, 0.0f);
-                                if (live && g < NV) a.Y[(size_t)n * a.R + row] = y;
+                        // A_i = lo + hi * 2^16 exactly: lo < 2^31 (unsigned), |hi| <= 2^30
+                        if (a.A) {
+                            if (live && il < m)
+                                a.A[((size_t)il * a.batch + n) * (size_t)a.R + row] =
+                                    (long long)(uint32_t)s.x + ((long long)s.y << 16);
+                            continue;
+                        }
+                        const double z = row_sum16((double)s_scales[il] * ((double)(uint32_t)s.x + (double)s.y * 65536.0));
+                        float y = (float)(z * a.out_scale);
+                        if (a.bias && live) y += a.bias[row];
+                        if (a.c_prev) {
+                            // LSTM cell: the four rows of the task are the gates i, f, g, o of one unit (row = unit
+                            // for gate i); lane 0 updates the unit
+                            const float gi = lane_value<0>(y), gf = lane_value<16>(y);
+                            const float gg = lane_value<32>(y), go = lane_value<48>(y);
+                            if (lane == 0 && live) {
+                                const size_t at = (size_t)n * a.gate_h + (size_t)row;
+                                const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
+                                a.c_out[at] = cn;
+                                a.h_out[at] = sigmoid_f(go) * tanhf(cn);
                             }
+                        } else {
+                            if (a.relu) y = fmaxf(y, 0.0f);
+                            if (live && il == 0) a.Y[(size_t)n * a.R + row] = y;
                         }
                     }
                     ++pr;
