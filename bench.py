@@ -247,6 +247,13 @@ def main():
         "roofline_other": other,
     }
 
+    out["same_gpu_references"] = same_gpu_references(torch, dev, W, X, per_m)
+    out["paper_reference"] = {
+        "what": "Table 1 of the paper: kernel speedup over a Cutlass fp32 matrix-vector product at 4096 x 4096, "
+                "batch 1, 32-bit activations; PBatch-n stores n + 1 bitlayers (bits_used = n + 1 here)",
+        "hardware": "NVIDIA Tesla T4 (the paper's; another machine: context, not a target)",
+        "speedup_vs_fp32": {"PBatch-1": 10.7, "PBatch-2": 8.3, "PBatch-4": 5.3, "PBatch-8": 3.1},
+        "stated_bound": "32 / (n + 1)"}
     if not args.no_batch:
         del pool, packed
         torch.cuda.empty_cache()
@@ -263,6 +270,43 @@ def main():
         with open(args.detail, "w") as f:
             json.dump(out, f, indent=1)
     print(line, flush=True)
+
+
+def same_gpu_references(torch, dev, W, X, per_m):
+    """Two reference points measured in this run on this GPU: (1) the bandwidth a plain elementwise kernel reaches
+    on 256 MiB (read + write), the practical ceiling next to the 8 TB/s of the data sheet; (2) the fp32
+    matrix-vector product the quantized one replaces (torch.mv = the vendor BLAS), cold weights, in a HIP graph,
+    and the speedup of every bits_used over it (the paper's Table 1 metric, here on one machine)."""
+    xc = torch.zeros(64 << 20, dtype=torch.float32, device=dev)
+    yc = torch.empty_like(xc)
+    torch.add(xc, 1.0, out=yc)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(10):
+        torch.add(xc, 1.0, out=yc)
+    e1.record()
+    torch.cuda.synchronize()
+    stream_gbps = 2 * xc.numel() * 4 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    del xc, yc
+    n = W.shape[0]
+    Wd = torch.from_numpy(W).to(dev)
+    copies = max(2, POOL_BYTES // (Wd.numel() * 4))
+    pool = [Wd] + [Wd.clone() for _ in range(copies - 1)]
+    xd = torch.from_numpy(X[0]).to(dev)
+    y = torch.empty(n, dtype=torch.float32, device=dev)
+
+    def f():
+        for i in range(copies):
+            torch.mv(pool[i], xd, out=y)
+    t = _graph_time(torch, f, 1) / copies
+    del pool, Wd
+    torch.cuda.empty_cache()
+    return {"stream_elementwise_GBps": round(stream_gbps, 1),
+            "fp32_matvec_us": round(t * 1e6, 2), "fp32_matvec_GBps": round(n * n * 4 / t / 1e9, 1),
+            "speedup_vs_fp32": {str(r["bits_used"]): round(t * 1e6 / r["us_per_call"], 2) for r in per_m},
+            "bound_32_over_bits_used": {str(r["bits_used"]): round(32.0 / r["bits_used"], 2) for r in per_m}}
 
 
 def measured_traffic(kernel, n, B):
