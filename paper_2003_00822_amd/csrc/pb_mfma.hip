@@ -188,19 +188,15 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 template <int NQ, int NV, int MAXS, int RU>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 {
-    // Units requested before the activations have arrived.  The memory pipeline of a CU serves requests in
-    // order, so the activation loads of the waves that start last queue behind every weight load issued before
-    // them: a small head start keeps HBM busy during the transpose, the rest of the ring follows once the planes
-    // are built.
-    constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
+    // Units requested before the activations have arrived (a head start that keeps HBM busy during the transpose);
+    // the rest of the ring follows once the planes are built.
+#ifndef PB_MFMA_PRE
+#define PB_MFMA_PRE 2
+#endif
+    constexpr int PRE = NQ >= 4 ? (PB_MFMA_PRE < 1 ? PB_MFMA_PRE : 1) : (RU < PB_MFMA_PRE ? RU : PB_MFMA_PRE);
     // (low 16 planes, high 16 planes) sums per vector, bitlayer and row; two buffers, used by alternate row tiles
     __shared__ int2 abuf[2][NV][PB_MAX_BITS][kTileRows];
     __shared__ float s_scales[PB_MAX_BITS];
-
-    // LDS sums start at zero (the only barrier that is not in step with the data: taken before any load is issued)
-    for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * kTileRows; i += blockDim.x)
-        (&abuf[0][0][0][0])[i] = make_int2(0, 0);
-    __syncthreads();
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -241,13 +237,23 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         else ld_soff += a.layer_step;
     };
 
+    // LDS sums start at zero.  The barrier that orders this is taken after every wave has REQUESTED its activations
+    // and before any wave requests weights: the memory pipeline of a CU returns data in request order, so an
+    // activation load queued behind another wave's weight loads (HBM misses) would arrive a memory latency late.
+    auto zero_sums_and_meet = [&]() {
+        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * kTileRows; i += blockDim.x)
+            (&abuf[0][0][0][0])[i] = make_int2(0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
     // ---- the planes of this wave's slice, expanded to A operands, kept in registers ----
     // lane l = 16 * kb + p: planes p (lo) and 16 + p (hi) of the words 16 * q + 4 * kb + t
     const int kb = lane >> 4;
     u32x4 pa_lo[NV][NQ][4], pa_hi[NV][NQ][4];
     if (a.planes) {
-#pragma unroll
-        for (int k = 0; k < PRE; ++k) issue(ring[k]);
+        uint4 plo[NV][NQ], phi[NV][NQ];
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const int n = min(n0 + v, a.batch - 1);
@@ -256,26 +262,33 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 a.planes + ((size_t)n * 32 + (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
-                uint4 lo = make_uint4(0, 0, 0, 0), hi = lo;
+                plo[v][q] = phi[v][q] = make_uint4(0, 0, 0, 0);
                 if (q < nq && live) {
-                    lo = *reinterpret_cast<const uint4 *>(pl + q * 16);
-                    hi = *reinterpret_cast<const uint4 *>(pl + (size_t)16 * a.cwp + q * 16);
+                    plo[v][q] = *reinterpret_cast<const uint4 *>(pl + q * 16);
+                    phi[v][q] = *reinterpret_cast<const uint4 *>(pl + (size_t)16 * a.cwp + q * 16);
                 }
+            }
+        }
+        zero_sums_and_meet();
+#pragma unroll
+        for (int k = 0; k < PRE; ++k) issue(ring[k]);
+#pragma unroll
+        for (int v = 0; v < NV; ++v)
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const uint4 lo = plo[v][q], hi = phi[v][q];
                 expand_plane(lo.x, pa_lo[v][q][0]); expand_plane(lo.y, pa_lo[v][q][1]);
                 expand_plane(lo.z, pa_lo[v][q][2]); expand_plane(lo.w, pa_lo[v][q][3]);
                 expand_plane(hi.x, pa_hi[v][q][0]); expand_plane(hi.y, pa_hi[v][q][1]);
                 expand_plane(hi.z, pa_hi[v][q][2]); expand_plane(hi.w, pa_hi[v][q][3]);
             }
-        }
     } else {
         // Algorithm 2: x_q = Int(x * 2^f); then the bitwise transpose, 32 columns x 32 bits at a time in each
         // half of the wave: lane (half H, column c) converts column c of word 16 q + 4 (2 H + e) + t, e = 0, 1.
         // V_PERMLANE16_SWAP hands the even rows of 16 lanes both 16-column halves of the e = 0 word and the odd
         // rows those of the e = 1 word, which is the first stage of the 32 x 32 transpose; the other four stages
         // stay inside a row.  Lane (kb, p) ends with planes p and 16 + p of word 16 q + 4 kb + t.
-        // The activations are fetched before the weight stream starts, so that waiting for them does not wait
-        // for the weights (loads return in order); buffer loads return 0 beyond the end of a vector, and for
-        // the vectors beyond the end of the batch.
+        // Buffer loads return 0 beyond the end of a vector, and for the vectors beyond the end of the batch.
         const int colb = (32 * (16 * q0 + 8 * (lane >> 5)) + (lane & 31)) * 4;   // byte offset of (q = 0, e = 0, t = 0)
         uint32_t xv[NV][NQ][4][2];
 #pragma unroll
@@ -293,12 +306,13 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         xv[v][q][t][e] =
                             __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
         }
+        // Second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range.
+        // Columns of the first part would have negative offsets here; those are clamped and the value dropped
+        // (a negative register offset that an instruction offset brings back above zero is not range-checked
+        // lane by lane on this hardware).
+        uint32_t xw[NV][NQ][4][2];
+        const int colb1 = colb - a.cols0 * 4;
         if (a.X1) {
-            // Second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range.
-            // Columns of the first part would have negative offsets here; those are clamped and the value dropped
-            // (a negative register offset that an instruction offset brings back above zero is not range-checked
-            // lane by lane on this hardware).
-            const int colb1 = colb - a.cols0 * 4;
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const int n = min(n0 + v, a.batch - 1);
@@ -310,17 +324,26 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
 #pragma unroll
-                        for (int e = 0; e < 2; ++e) {
-                            const int off = colb1 + 128 * (16 * q + 4 * e + t);
-                            const uint32_t w = __builtin_amdgcn_raw_buffer_load_b32(rx1, max(off, 0), 0, 0);
-                            xv[v][q][t][e] |= off >= 0 ? w : 0u;
-                        }
+                        for (int e = 0; e < 2; ++e)
+                            xw[v][q][t][e] = __builtin_amdgcn_raw_buffer_load_b32(
+                                rx1, max(colb1 + 128 * (16 * q + 4 * e + t), 0), 0, 0);
             }
         }
-        __builtin_amdgcn_sched_barrier(0x7);
+        zero_sums_and_meet();
 #pragma unroll
         for (int k = 0; k < PRE; ++k) issue(ring[k]);
         const TransposeConsts tc = transpose_consts(lane);
+        if (a.X1) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int e = 0; e < 2; ++e)
+                            xv[v][q][t][e] |= colb1 + 128 * (16 * q + 4 * e + t) >= 0 ? xw[v][q][t][e] : 0u;
+        }
 #pragma unroll
         for (int v = 0; v < NV; ++v)
 #pragma unroll
