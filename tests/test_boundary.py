@@ -119,6 +119,31 @@ def test_null_and_range_arguments_rejected_before_launch(pb):
                           null) == pb.PB_EINVAL
 
 
+def test_gate_interleaved_layout_sizes_and_checks(pb):
+    gates = pb.PB_LAYOUT_TILE16_GATES_V1
+    # H = 1500: 375 row tiles of 4 hidden units (16 gate rows), 3000 columns -> 6 chunks of 16 words
+    d = pb.pb_desc_init_layout(6000, 3000, 4, gates)
+    assert pb.pb_packed_bytes(d) == 4 * 375 * 16 * 96 * 4
+    # H = 5: two row tiles, the second one mostly padding
+    d = pb.pb_desc_init_layout(20, 12, 2, gates)
+    assert pb.pb_packed_bytes(d) == 2 * 2 * 16 * 16 * 4
+    with pytest.raises(pb.PbError):
+        pb.pb_desc_init_layout(10, 64, 4, gates)          # rows not a multiple of 4
+
+
+def test_bias_act_arguments_rejected_before_launch(pb):
+    L = pb.lib()
+    d = pb.pb_desc_init(64, 64, 4)
+    dp = ctypes.byref(d)
+    fake = ctypes.c_void_p(0x1000)
+    odd = ctypes.c_void_p(0x1004)
+    null = ctypes.c_void_p(0)
+    assert L.pb_matmul_bias_act(fake, fake, dp, 4, fake, 1, null, 2, fake, fake, null) == pb.PB_EINVAL   # bad activation
+    assert L.pb_matmul_bias_act(fake, fake, dp, 4, fake, 1, odd, 1, fake, fake, null) == pb.PB_EALIGN    # bias alignment
+    assert L.pb_matmul_bias_act(fake, fake, dp, 4, fake, 1, null, 1, null, fake, null) == pb.PB_EINVAL   # Y null
+    assert L.pb_matmul_bias_act(fake, fake, dp, 5, fake, 1, null, 0, fake, fake, null) == pb.PB_EINVAL   # bits_used
+
+
 def test_strerror(pb):
     assert pb.strerror(0) == "ok"
     for s in (pb.PB_EINVAL, pb.PB_EALIGN, pb.PB_ESIZE, pb.PB_EHIP):
