@@ -248,6 +248,8 @@ def main():
     }
 
     out["same_gpu_references"] = same_gpu_references(torch, dev, W, X, per_m)
+    if mfma:
+        out["table1_analog"] = table1_analog(torch, pb, dev, W, X, out["same_gpu_references"]["fp32_matvec_us"])
     out["paper_reference"] = {
         "what": "Table 1 of the paper: kernel speedup over a Cutlass fp32 matrix-vector product at 4096 x 4096, "
                 "batch 1, 32-bit activations; PBatch-n stores n + 1 bitlayers (bits_used = n + 1 here)",
@@ -270,6 +272,34 @@ def main():
         with open(args.detail, "w") as f:
             json.dump(out, f, indent=1)
     print(line, flush=True)
+
+
+def table1_analog(torch, pb, dev, W, X, fp32_us):
+    """The layout of the paper's Table 1 on this GPU: PBatch-n = n + 1 stored bitlayers, all used, with 8-, 16-
+    and 32-bit fixed-point activations (frac_bits 4 / 12 / 16, so that x ~ N(0,1) keeps a few integer bits),
+    4096 x 4096, batch 1, cold weights; speedup over the fp32 matrix-vector product measured in this run."""
+    n = W.shape[0]
+    Wd = torch.from_numpy(W).to(dev)
+    Xd = torch.from_numpy(X).to(dev)
+    Y = torch.empty((1, n), dtype=torch.float32, device=dev)
+    rows = []
+    for nbits in (1, 2, 4, 8):
+        B = nbits + 1
+        for (k, f) in ((8, 4), (16, 12), (32, 16)):
+            lin = pb.PackedLinear(Wd, B, frac_bits=f, act_bits=k)
+            copies = max(2, POOL_BYTES // lin.packed.numel())
+            copies = min(copies, 96)
+            pool = [lin.packed] + [lin.packed.clone() for _ in range(copies - 1)]
+
+            def f_():
+                for i in range(copies):
+                    pb.pb_matmul(pool[i], lin.scales, lin.desc, B, Xd, 1, Y, lin.workspace)
+            t = _graph_time(torch, f_, 1) / copies
+            rows.append({"method": "PBatch-%d" % nbits, "bitlayers": B, "act_bits": k, "us_per_call": round(t * 1e6, 2),
+                         "speedup_vs_fp32": round(fp32_us / (t * 1e6), 2), "bound": round(32.0 / B, 2)})
+            del pool, lin
+    torch.cuda.empty_cache()
+    return {"workload": "FC 4096x4096, batch 1, bits_used = bitlayers", "fp32_matvec_us": fp32_us, "rows": rows}
 
 
 def same_gpu_references(torch, dev, W, X, per_m):

@@ -185,7 +185,10 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 // the registers a wave may use; RU: units (row tile, bitlayer) whose blocks a wave has in flight.  The host picks
 // RU <= the units a wave has, so that a short stream pays for no empty ring slots; 4 KB in flight per wave
 // measured best (more requests in flight than that slow the short streams down and do not speed up the long ones).
-template <int NQ, int NV, int MAXS, int RU>
+// HI: planes 16-31 are computed.  Activations of at most 16 bits (Section 3.1: k = 8, 16) have planes 15-31 all
+// equal to their sign plane, which together weigh -2^15: one matrix instruction per step instead of two, half the
+// transpose, same integers.
+template <int NQ, int NV, int MAXS, int RU, bool HI>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 {
     // Units requested before the activations have arrived (a head start that keeps HBM busy during the transpose);
@@ -279,8 +282,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 const uint4 lo = plo[v][q], hi = phi[v][q];
                 expand_plane(lo.x, pa_lo[v][q][0]); expand_plane(lo.y, pa_lo[v][q][1]);
                 expand_plane(lo.z, pa_lo[v][q][2]); expand_plane(lo.w, pa_lo[v][q][3]);
-                expand_plane(hi.x, pa_hi[v][q][0]); expand_plane(hi.y, pa_hi[v][q][1]);
-                expand_plane(hi.z, pa_hi[v][q][2]); expand_plane(hi.w, pa_hi[v][q][3]);
+                if (HI) {
+                    expand_plane(hi.x, pa_hi[v][q][0]); expand_plane(hi.y, pa_hi[v][q][1]);
+                    expand_plane(hi.z, pa_hi[v][q][2]); expand_plane(hi.w, pa_hi[v][q][3]);
+                }
             }
     } else {
         // Algorithm 2: x_q = Int(x * 2^f); then the bitwise transpose, 32 columns x 32 bits at a time in each
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     const uint32_t lo = (c_lo & 0xFFFFu) | (c_hi << 16);         // bits 0-15 of the 32 columns
                     const uint32_t hi = (c_hi & 0xFFFF0000u) | (c_lo >> 16);     // bits 16-31
                     expand_plane(bit_transpose16(lo, tc), pa_lo[v][q][t]);
-                    expand_plane(bit_transpose16(hi, tc), pa_hi[v][q][t]);
+                    if (HI) expand_plane(bit_transpose16(hi, tc), pa_hi[v][q][t]);
                 }
     }
     if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
@@ -375,6 +380,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         kl[c] = (float)(1 << (4 * kb + c));
         kh[c] = (kb == 3 && c == 3) ? -kl[c] : kl[c];    // plane 31 weighs -2^31 (Algorithm 2)
     }
+    if (!HI && kb == 3) kl[3] = -kl[3];                  // 16-bit activations: plane 15 stands for planes 15-31, -2^15
 
     const int j = lane & 15;
     int pi = 0, pr = 0;   // bitlayer and round of the unit being multiplied
@@ -395,7 +401,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                         for (int v = 0; v < NV; ++v) {
                             acc_lo[v] = mfma_fp4(as_operand(pa_lo[v][q][t]), b, acc_lo[v]);
-                            acc_hi[v] = mfma_fp4(as_operand(pa_hi[v][q][t]), b, acc_hi[v]);
+                            if (HI) acc_hi[v] = mfma_fp4(as_operand(pa_hi[v][q][t]), b, acc_hi[v]);
                         }
                     }
                 }
@@ -409,7 +415,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                                        acc_hi[v][3] * kh[3];
                     int2 *dst = &abuf[pr & 1][v][pi][j];
                     atomicAdd(&dst->x, (int)lo_f);
-                    atomicAdd(&dst->y, (int)hi_f);
+                    if (HI) atomicAdd(&dst->y, (int)hi_f);
                 }
                 if (++pi == m) {
                     // The row tile is complete in every slice: scale and store it.  (The barrier per row tile also
@@ -432,14 +438,15 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                             s = *src;
                             *src = make_int2(0, 0);
                         }
-                        // A_i = lo + hi * 2^16 exactly: lo < 2^31 (unsigned), |hi| <= 2^30
+                        // A_i = lo + hi * 2^16 exactly: 0 <= lo < 2^31 (unsigned), |hi| <= 2^30; with 16 planes lo
+                        // carries the sign plane itself, |lo| < 2^30, and hi is 0
+                        const long long lo = HI ? (long long)(uint32_t)s.x : (long long)s.x;
                         if (a.A) {
                             if (live && il < m)
-                                a.A[((size_t)il * a.batch + n) * (size_t)a.R + row] =
-                                    (long long)(uint32_t)s.x + ((long long)s.y << 16);
+                                a.A[((size_t)il * a.batch + n) * (size_t)a.R + row] = lo + ((long long)s.y << 16);
                             continue;
                         }
-                        const double z = row_sum16((double)s_scales[il] * ((double)(uint32_t)s.x + (double)s.y * 65536.0));
+                        const double z = row_sum16((double)s_scales[il] * ((double)lo + (double)s.y * 65536.0));
                         float y = (float)(z * a.out_scale);
                         if (a.bias && live) y += a.bias[row];
                         if (a.c_prev) {
@@ -469,9 +476,11 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 // The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup, ring depth in units).
 struct Variant {
     int nq, nv, maxs, ru;
-    const void *fn;
+    const void *fn, *fn16;    // 32 planes, 16 planes
 };
-#define PB_VARIANT(NQ, NV, MAXS, RU) {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU>)}
+#define PB_VARIANT(NQ, NV, MAXS, RU)                                                          \
+    {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true>),        \
+     reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false>)}
 static const Variant kVariants[] = {
     PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
     PB_VARIANT(1, 2, 8, 1),  PB_VARIANT(1, 2, 8, 2),  PB_VARIANT(1, 2, 8, 4),
@@ -569,7 +578,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
     void *args[] = {&a};
-    const hipError_t e = hipLaunchKernel(kVariants[pick_ring(vi, a.rounds_per_wg * bits_used)].fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
+    const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * bits_used)];
+    const hipError_t e = hipLaunchKernel(act_bits > 16 ? run.fn : run.fn16, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
                                          0, st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
 }

@@ -153,6 +153,16 @@ def test_prepared_halves_equal_whole_call(pb, layout):
     assert (Y2.cpu().numpy().view(np.int32) == Y1.view(np.int32)).all()
 
 
+@pytest.mark.parametrize("fk", [(6, 8), (10, 16), (14, 16)])
+def test_sixteen_plane_variant_with_batch_and_saturation(pb, fk):
+    """act_bits <= 16 runs the 16-plane variant of the matrix-core kernel; wide inputs saturate at k bits."""
+    f, k = fk
+    W, X = synth.ragged(90, 1300, batch=5, case=23, xdist="wide")
+    run_layer(pb, W, 6, X, [1, 4, 6], frac_bits=f, act_bits=k, layout=LAYOUTS["mfma"])
+    W, X = synth.ragged(40, 5000, batch=1, case=29, xdist="normal")
+    run_layer(pb, W, 3, X, [3], frac_bits=f, act_bits=k, layout=LAYOUTS["mfma"])
+
+
 def test_config1_fc_1024_definition_level(pb, layout):
     """Config 1, checked against the byte-per-bit tier of the oracle (Algorithm 2 taken literally)."""
     W, X = synth.fc_small()
