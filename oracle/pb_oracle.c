@@ -18,6 +18,11 @@
  * Parity unpinned (definitions by choice, the paper prints no values for them):
  *   - pbo_quantize: symmetric step d = max|W| / (2^(B-1)-1), round-half-even;
  *     only invariants are pinned.
+ *   - pbo_quantize_mode: the three other quantizers of Section 3.3 (the
+ *     printed range formula, the 1-bit +-1 code, the clipping search); the
+ *     paper gives the formula of the first only, the scale of the second and
+ *     the error measure and candidate set of the third are readings; only
+ *     invariants are pinned.
  *   - pbo_fixed_point: saturation and NaN rule of the fp32 -> fixed cast.
  */
 #include <math.h>
@@ -55,6 +60,104 @@ int pbo_quantize(const float *W, int64_t n, int bits, int32_t *q, float *d_out)
     }
     *d_out = d;
     return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Section 3.3, the other quantizers it describes.  All keep the grid linearly
+ * spaced (Q(W) = d * q, q a B-bit two's-complement code), so the bitlayers and
+ * scales follow from (q, d) exactly as for pbo_quantize.
+ *
+ * mode 1, "range": the printed formula, d = (max(W) - min(W)) / 2^n with
+ *   n = B - 1 magnitude bits (PBatch-n stores n + 1 layers), q = round(W / d)
+ *   clamped to the code range [-2^n, 2^n - 1]; d = 1 if max = min.
+ * mode 2, "sign": "for quantizing to 1 bit ... exclude representing 0 and
+ *   instead ... represent a positive and negative value": q = +1 for W >= 0,
+ *   -1 otherwise (B = 2: sign layer + one magnitude layer).  The paper gives
+ *   no scale; reading: d = mean|W| (the least-squares scale of a sign code).
+ * mode 3, "clip": "optimize over a clipping threshold to find a quantized
+ *   matrix with the smallest mean error versus the full precision weight
+ *   matrix".  Reading: thresholds T_k = max|W| * k / 32, k = 1..32; for each,
+ *   the symmetric quantizer with d_k = T_k / (2^(B-1) - 1) and clamping; the
+ *   error is the mean of |W - d_k q|; the smallest wins, the larger threshold
+ *   on a tie.
+ * So that a parallel implementation can reproduce the sums bit for bit, the two
+ * means are taken over values truncated to multiples of 2^(e-30), where
+ * 2^e <= max|W| < 2^(e+1): integers below 2^31, summed exactly in 64 bits
+ * (n <= 2^32 elements).  fp32 products and differences are rounded separately
+ * (compiled without contraction). */
+static uint64_t pbo_fix30(float a, int e) /* trunc(|a| * 2^(30-e)), a finite, |a| < 2^(e+1) */
+{
+    float t = truncf(ldexpf(fabsf(a), 30 - e));
+    return (t != t) ? 0u : (uint64_t)t;
+}
+
+static int32_t pbo_round_clamp(float w, float d, int32_t qmin, int32_t qmax)
+{
+    float r = rintf(w / d);
+    if (r != r) return 0;
+    if (r >= (float)qmax) return qmax;
+    if (r <= (float)qmin) return qmin;
+    return (int32_t)r;
+}
+
+int pbo_quantize_mode(const float *W, int64_t n, int bits, int mode, int32_t *q, float *d_out)
+{
+    if (bits < 1 || bits > 16 || n < 1) return -1;
+    if (mode == 0) return pbo_quantize(W, n, bits, q, d_out);
+    float M = 0.0f, hi = -INFINITY, lo = INFINITY;
+    for (int64_t i = 0; i < n; ++i) {
+        float w = W[i];
+        if (w != w) continue;
+        if (fabsf(w) > M) M = fabsf(w);
+        if (w > hi) hi = w;
+        if (w < lo) lo = w;
+    }
+    int32_t qmax = (1 << (bits - 1)) - 1, qmin = -(1 << (bits - 1));
+    int e = 0;
+    if (M > 0.0f) (void)frexpf(M, &e), e -= 1; /* M = f * 2^(e+1), 0.5 <= f < 1  ->  2^e <= M */
+    if (mode == 1) {
+        float d = (hi > lo) ? (hi - lo) / (float)(1 << (bits - 1)) : 1.0f;
+        for (int64_t i = 0; i < n; ++i) q[i] = pbo_round_clamp(W[i], d, qmin, qmax);
+        *d_out = d;
+        return 0;
+    }
+    if (mode == 2) {
+        if (bits != 2) return -1;
+        uint64_t S = 0;
+        for (int64_t i = 0; i < n; ++i) {
+            if (W[i] != W[i]) { q[i] = 1; continue; }
+            S += pbo_fix30(W[i], e);
+            q[i] = (W[i] >= 0.0f) ? 1 : -1;
+        }
+        *d_out = (float)(ldexp((double)S, e - 30) / (double)n);
+        return 0;
+    }
+    if (mode == 3) {
+        int32_t qm = qmax > 0 ? qmax : 1;
+        if (M == 0.0f) {
+            for (int64_t i = 0; i < n; ++i) q[i] = 0;
+            *d_out = 1.0f;
+            return 0;
+        }
+        int best = 32;
+        uint64_t best_err = 0;
+        for (int k = 32; k >= 1; --k) {
+            float T = M * ((float)k * 0.03125f);
+            float d = T / (float)qm;
+            uint64_t E = 0;
+            for (int64_t i = 0; i < n; ++i) {
+                if (W[i] != W[i]) continue;
+                float p = d * (float)pbo_round_clamp(W[i], d, qmin, qmax);
+                E += pbo_fix30(W[i] - p, e);
+            }
+            if (k == 32 || E < best_err) { best = k; best_err = E; }
+        }
+        float d = (M * ((float)best * 0.03125f)) / (float)qm;
+        for (int64_t i = 0; i < n; ++i) q[i] = pbo_round_clamp(W[i], d, qmin, qmax);
+        *d_out = d;
+        return 0;
+    }
+    return -1;
 }
 
 /* ------------------------------------------------------------------------ */

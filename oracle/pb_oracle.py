@@ -42,6 +42,8 @@ def lib():
         L = ctypes.CDLL(_LIB)
         L.pbo_quantize.argtypes = [_P, c_i64, c_int, _P, _P]
         L.pbo_quantize.restype = c_int
+        L.pbo_quantize_mode.argtypes = [_P, c_i64, c_int, c_int, _P, _P]
+        L.pbo_quantize_mode.restype = c_int
         L.pbo_bitlayers.argtypes = [_P, c_i64, c_int, _P, _P]
         L.pbo_bitlayers.restype = c_int
         L.pbo_scales.argtypes = [c_f32, c_int, _P]
@@ -93,6 +95,20 @@ def quantize(W, bits):
     rc = lib().pbo_quantize(_ptr(W), W.size, bits, _ptr(q), _ptr(d))
     if rc:
         raise ValueError("pbo_quantize rc=%d" % rc)
+    return q, d[0]
+
+
+QUANT_SYMMETRIC, QUANT_RANGE, QUANT_SIGN, QUANT_CLIP = 0, 1, 2, 3
+
+
+def quantize_mode(W, bits, mode):
+    """Section 3.3's other quantizers (1 = printed range formula, 2 = 1-bit +-1 code, 3 = clipping search)."""
+    W = _c(W, np.float32)
+    q = np.empty(W.shape, dtype=np.int32)
+    d = np.zeros(1, dtype=np.float32)
+    rc = lib().pbo_quantize_mode(_ptr(W), W.size, bits, mode, _ptr(q), _ptr(d))
+    if rc:
+        raise ValueError("pbo_quantize_mode rc=%d" % rc)
     return q, d[0]
 
 
@@ -244,8 +260,8 @@ def lstm_pointwise(gates, bias, c_prev):
     return h, c
 
 
-def prepare(W, bits):
+def prepare(W, bits, mode=0):
     """Algorithm 1 as a whole: -> dict(q, d, layers, s, scales)."""
-    q, d = quantize(W, bits)
+    q, d = quantize(W, bits) if mode == 0 else quantize_mode(W, bits, mode)
     layers, s = bitlayers(q, bits)
     return {"q": q, "d": d, "layers": layers, "s": s, "scales": scales(d, bits), "bits": bits}

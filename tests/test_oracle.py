@@ -336,3 +336,100 @@ def test_lstm_pointwise_matches_torch_cell():
     h, c = po.lstm_pointwise(gates, b.astype(np.float32), c0.astype(np.float32))
     assert np.abs(h - h1.numpy()).max() < 2e-6
     assert np.abs(c - c1.numpy()).max() < 2e-6
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# Section 3.3's other quantizers (oracle readings; the paper prints no values: closed forms, brute force, invariants)
+
+def test_range_quantizer_hand_values():
+    # d = (max - min) / 2^n with n = B - 1: W = [-1, 0, 1, 3], B = 3 -> d = 1, codes = W
+    W = np.array([-1.0, 0.0, 1.0, 3.0], dtype=np.float32)
+    q, d = po.quantize_mode(W, 3, po.QUANT_RANGE)
+    assert d == 1.0 and q.tolist() == [-1, 0, 1, 3]
+    # B = 2 -> d = 2: W / d = [-0.5, 0, 0.5, 1.5] -> round half to even [0, 0, 0, 2], clamped to the code range [-2, 1]
+    q, d = po.quantize_mode(W, 2, po.QUANT_RANGE)
+    assert d == 2.0 and q.tolist() == [0, 0, 0, 1]
+    # one-signed weights overflow the range and are clamped (the reason the default quantizer is symmetric)
+    W = np.array([0.0, 1.0, 2.0, 3.0, 4.0], dtype=np.float32)
+    q, d = po.quantize_mode(W, 3, po.QUANT_RANGE)
+    assert d == 1.0 and q.tolist() == [0, 1, 2, 3, 3]
+    # constant matrix: d = 1
+    q, d = po.quantize_mode(np.full(5, 0.25, dtype=np.float32), 4, po.QUANT_RANGE)
+    assert d == 1.0 and q.tolist() == [0] * 5
+
+
+def test_sign_quantizer_hand_values_and_mean():
+    W = np.array([0.5, -1.5, 2.0, -4.0], dtype=np.float32)
+    q, d = po.quantize_mode(W, 2, po.QUANT_SIGN)
+    assert q.tolist() == [1, -1, 1, -1] and d == 2.0            # mean |W| = 8 / 4
+    layers, s = po.bitlayers(q, 2)
+    assert s.tolist() == [-2, 1]
+    assert layers.tolist() == [[0, 1, 0, 1], [1, 1, 1, 1]]       # +1 = (0, 1), -1 = (1, 1): no code is 0
+    with pytest.raises(ValueError):
+        po.quantize_mode(W, 3, po.QUANT_SIGN)
+    rng = np.random.default_rng(5)
+    W = rng.normal(0, 0.05, size=5000).astype(np.float32)
+    q, d = po.quantize_mode(W, 2, po.QUANT_SIGN)
+    assert set(np.unique(q).tolist()) == {-1, 1} and (q == np.where(W >= 0, 1, -1)).all()
+    exact = np.abs(W.astype(np.float64)).mean()
+    assert abs(float(d) - exact) <= 2.0 ** -28 * np.abs(W).max() + 1e-7 * exact    # truncation to 2^(e-30) per term
+    # the least-squares property of that scale: no other scale has a smaller squared error
+    err = lambda t: ((W.astype(np.float64) - t * q) ** 2).sum()
+    assert err(float(d)) <= min(err(float(d) * 1.01), err(float(d) * 0.99))
+
+
+def _clip_search_brute_force(W, bits):
+    """The clipping search spelled out with numpy fp32 scalars and Python integers."""
+    f32 = np.float32
+    M = f32(np.abs(W).max())
+    e = int(np.floor(np.log2(float(M))))
+    qmax, qmin = (1 << (bits - 1)) - 1, -(1 << (bits - 1))
+    qm = f32(max(qmax, 1))
+    best = None
+    for k in range(32, 0, -1):
+        d = f32(f32(M * f32(f32(k) * f32(0.03125))) / qm)
+        q = np.clip(np.rint((W / d).astype(np.float32)), qmin, qmax).astype(np.int32)
+        resid = np.abs((W - (d * q.astype(np.float32)).astype(np.float32)).astype(np.float32))
+        E = sum(int(np.trunc(np.ldexp(np.float64(v), 30 - e))) for v in resid)
+        if best is None or E < best[0]:
+            best = (E, k, d, q)
+    return best
+
+
+@pytest.mark.parametrize("bits", [1, 2, 3, 4, 8])
+def test_clip_search_against_brute_force(bits):
+    rng = np.random.default_rng(40 + bits)
+    W = rng.normal(0, 0.05, size=400).astype(np.float32)
+    W[7] = 1.0                                                   # an outlier: clipping pays off
+    E, k, d_ref, q_ref = _clip_search_brute_force(W, bits)
+    q, d = po.quantize_mode(W, bits, po.QUANT_CLIP)
+    assert d == d_ref and (q == q_ref).all()
+    if bits >= 3:
+        assert k < 32
+        # and the true mean error is no larger than without clipping
+        q0, d0 = po.quantize(W, bits)
+        mae = lambda qq, dd: np.abs(W.astype(np.float64) - float(dd) * qq).mean()
+        assert mae(q, d) <= mae(q0, d0)
+
+
+def test_clip_search_keeps_an_exact_grid():
+    # weights already on the grid of the unclipped quantizer: zero error at k = 32, nothing smaller exists
+    bits = 4
+    codes = np.arange(-7, 8, dtype=np.float32)
+    W = (codes * np.float32(0.125)).astype(np.float32)
+    q, d = po.quantize_mode(W, bits, po.QUANT_CLIP)
+    assert d == np.float32(0.125) and (q == codes.astype(np.int32)).all()
+    q, d = po.quantize_mode(np.zeros(9, dtype=np.float32), bits, po.QUANT_CLIP)
+    assert d == 1.0 and not q.any()
+
+
+@pytest.mark.parametrize("mode", [1, 2, 3])
+def test_quantizer_variants_feed_algorithm_1_unchanged(mode):
+    """Whatever the quantizer, bitlayers and scales reconstruct d * q (Section 3.3: any linearly spaced grid)."""
+    rng = np.random.default_rng(60 + mode)
+    W = rng.normal(0, 0.3, size=(6, 40)).astype(np.float32)
+    bits = 2 if mode == 2 else 5
+    prep = po.prepare(W, bits, mode)
+    rec = np.tensordot(prep["s"], prep["layers"].astype(np.int64), axes=1)
+    assert (rec == prep["q"]).all()
+    assert np.allclose(prep["scales"], float(prep["d"]) * prep["s"].astype(np.float64), rtol=0, atol=0)
