@@ -110,6 +110,23 @@ int pb_quantize_pack(const float *W, int rows, int cols, int bits, void *packed,
  * descriptor pb_desc_init(rows, cols, bits) gives. */
 int pb_quantize_pack_desc(const float *W, const pb_desc *d, void *packed, float *scales, void *stream);
 
+/* The other quantizers of Section 3.3, same outputs as pb_quantize_pack_desc (q = B-bit codes on a linearly spaced
+ * grid, scales[i] = step * s_i):
+ *   PB_QUANT_SYMMETRIC    step = max|W| / (2^(B-1) - 1): what pb_quantize_pack does
+ *   PB_QUANT_RANGE        the printed formula, step = (max W - min W) / 2^(B-1), codes clamped to the B-bit range
+ *   PB_QUANT_SIGN         "for quantizing to 1 bit ... exclude representing 0": q = +1 (W >= 0) or -1,
+ *                         step = mean |W|; needs bits = 2 (sign layer + one magnitude layer)
+ *   PB_QUANT_CLIP_SEARCH  "optimize over a clipping threshold": the symmetric quantizer with the threshold
+ *                         max|W| * k / 32 (k = 1..32) whose mean |W - step * q| is smallest
+ * PB_EINVAL for an unknown quantizer or PB_QUANT_SIGN with bits != 2. */
+typedef enum pb_quantizer {
+    PB_QUANT_SYMMETRIC = 0,
+    PB_QUANT_RANGE = 1,
+    PB_QUANT_SIGN = 2,
+    PB_QUANT_CLIP_SEARCH = 3
+} pb_quantizer;
+int pb_quantize_pack_mode(const float *W, const pb_desc *d, int quantizer, void *packed, float *scales, void *stream);
+
 /* Inverse of the packing, for checking: q[r][c] = the B-bit code stored for
  * element (r, c), sign-extended to int32.  q: [rows][cols], written. */
 int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);

@@ -73,15 +73,22 @@ size_t pb_workspace_bytes(const pb_desc *d, int batch)
     return pb::workspace_bytes(L, batch);
 }
 
-int pb_quantize_pack_desc(const float *W, const pb_desc *d, void *packed, float *scales, void *stream)
+int pb_quantize_pack_mode(const float *W, const pb_desc *d, int quantizer, void *packed, float *scales, void *stream)
 {
     pb::Layout L;
     int rc = check_desc(d, &L);
     if (rc != PB_OK) return rc;
     if (!W || !packed || !scales) return PB_EINVAL;
+    if (quantizer < PB_QUANT_SYMMETRIC || quantizer > PB_QUANT_CLIP_SEARCH) return PB_EINVAL;
+    if (quantizer == PB_QUANT_SIGN && d->bits != 2) return PB_EINVAL;
     if (!aligned16(W) || !aligned16(packed) || !aligned16(scales)) return PB_EALIGN;
-    return hip_status(pb::launch_quantize_pack(W, L, static_cast<uint32_t *>(packed), scales,
+    return hip_status(pb::launch_quantize_pack(W, L, quantizer, static_cast<uint32_t *>(packed), scales,
                                                static_cast<hipStream_t>(stream)));
+}
+
+int pb_quantize_pack_desc(const float *W, const pb_desc *d, void *packed, float *scales, void *stream)
+{
+    return pb_quantize_pack_mode(W, d, PB_QUANT_SYMMETRIC, packed, scales, stream);
 }
 
 int pb_quantize_pack(const float *W, int rows, int cols, int bits, void *packed, float *scales, void *stream)

@@ -9,7 +9,8 @@
 namespace pb {
 
 // pb_quantize.hip
-int launch_quantize_pack(const float *W, const Layout &L, uint32_t *packed, float *scales, hipStream_t st);
+int launch_quantize_pack(const float *W, const Layout &L, int quantizer, uint32_t *packed, float *scales,
+                         hipStream_t st);
 int launch_unpack(const uint32_t *packed, const Layout &L, int32_t *q, hipStream_t st);
 
 // pb_prep.hip: fp32 activations -> fixed point -> bit planes + plane statistics.

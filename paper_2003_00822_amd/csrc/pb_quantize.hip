@@ -9,43 +9,59 @@
 
 namespace pb {
 
-__global__ void k_fill_u32(uint32_t *p, size_t n, uint32_t v)
+// Scratch for the reductions of the quantizers: 64 uint64 at the start of `packed` (every packed matrix is at
+// least 512 bytes; the packing kernel overwrites them last).
+enum { kSlotAbsMax = 0, kSlotMax = 1, kSlotMin = 2, kSlotAbsSum = 3, kSlotClip = 4, kScratchWords = 64 };
+constexpr int kClipSteps = 32;
+
+__global__ void k_fill_u64(unsigned long long *p, int n, unsigned long long v)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
-    for (; i < n; i += stride) p[i] = v;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = (i == kSlotMin) ? ~0ull : v;
 }
 
-// max |W| as the bit pattern of a non-negative float (orders like an unsigned integer)
-__global__ __launch_bounds__(256) void k_absmax(const float *__restrict__ W, size_t n, uint32_t *slot)
+// a float as an unsigned key that orders like the float (NaN excluded by the caller)
+__device__ __forceinline__ uint32_t ordered_key(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float from_ordered_key(uint32_t k)
+{
+    return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
+}
+
+// max |W|, max W and min W in one pass (Section 3.3: the step of every quantizer comes from these)
+__global__ __launch_bounds__(256) void k_stats(const float *__restrict__ W, size_t n, unsigned long long *scratch)
 {
     size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t stride = (size_t)gridDim.x * blockDim.x;
-    uint32_t m = 0;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    uint32_t am = 0, hi = 0, lo = 0xFFFFFFFFu;
     for (; i < n; i += stride) {
-        float a = fabsf(W[i]);
-        if (a == a) {
-            uint32_t b = __float_as_uint(a);
-            m = b > m ? b : m;
+        const float w = W[i];
+        if (w == w) {
+            const uint32_t a = __float_as_uint(fabsf(w)), k = ordered_key(w);
+            am = a > am ? a : am;
+            hi = k > hi ? k : hi;
+            lo = k < lo ? k : lo;
         }
     }
     for (int off = 32; off > 0; off >>= 1) {
-        uint32_t o = (uint32_t)__shfl_xor((int)m, off, 64);
-        m = o > m ? o : m;
+        const uint32_t a = (uint32_t)__shfl_xor((int)am, off, 64), h = (uint32_t)__shfl_xor((int)hi, off, 64);
+        const uint32_t l = (uint32_t)__shfl_xor((int)lo, off, 64);
+        am = a > am ? a : am;
+        hi = h > hi ? h : hi;
+        lo = l < lo ? l : lo;
     }
-    if ((threadIdx.x & 63) == 0 && m != 0) atomicMax(slot, m);
+    if ((threadIdx.x & 63) == 0) {
+        atomicMax(&scratch[kSlotAbsMax], (unsigned long long)am);
+        atomicMax(&scratch[kSlotMax], (unsigned long long)hi);
+        atomicMin(&scratch[kSlotMin], (unsigned long long)lo);
+    }
 }
 
-__device__ __forceinline__ float grid_step(float M, int bits)
+__device__ __forceinline__ int quantize_code(float w, float d, int qmin, int qmax)
 {
-    int qmax = (1 << (bits - 1)) - 1;
-    return (M == 0.0f) ? 1.0f : M / (float)(qmax > 0 ? qmax : 1);
-}
-
-__device__ __forceinline__ int quantize_code(float w, float d, int bits)
-{
-    int qmax = (1 << (bits - 1)) - 1;
-    int qmin = -(1 << (bits - 1));
     float r = rintf(w / d);  // IEEE divide, round half to even
     if (r != r) return 0;
     if (r >= (float)qmax) return qmax;
@@ -53,42 +69,136 @@ __device__ __forceinline__ int quantize_code(float w, float d, int bits)
     return (int)r;
 }
 
-// one thread per (padded row, padded word): builds that word of every bitlayer
-__global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint32_t layout, int rows, int cols,
-                                              int bits, int cw, int cwp, int rows_p, int gate_h, size_t layer_words,
-                                              const uint32_t *__restrict__ absmax_slot, uint32_t *__restrict__ packed)
+// trunc(|a| * 2^(30 - e)) for |a| < 2^(e + 1): an integer below 2^31, so that the sums below are exact in 64 bits
+// and do not depend on the order of the additions
+__device__ __forceinline__ unsigned long long fix30(float a, int e)
 {
-    size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    size_t total = (size_t)rows_p * (size_t)cwp;
-    if (idx >= total) return;
-    const int pr = (int)(idx / (size_t)cwp);       // packed row
-    int w = (int)(idx % (size_t)cwp);
-    const int r = gate_h ? gates_matrix_row(pr, gate_h) : pr;   // matrix row (-1 or >= rows: padding)
-    uint32_t wd[PB_MAX_BITS];
+    const float t = truncf(ldexpf(fabsf(a), 30 - e));
+    return (t != t) ? 0ull : (unsigned long long)t;
+}
+
+__device__ __forceinline__ unsigned long long wave_sum_u64(unsigned long long v)
+{
+    for (int off = 32; off > 0; off >>= 1) {
+        const uint32_t lo = (uint32_t)__shfl_xor((int)(uint32_t)v, off, 64);
+        const uint32_t hi = (uint32_t)__shfl_xor((int)(uint32_t)(v >> 32), off, 64);
+        v += ((unsigned long long)hi << 32) | lo;
+    }
+    return v;
+}
+
+// 1-bit +-1 code (Section 3.3): sum of |W| for the scale d = mean |W|
+__global__ __launch_bounds__(256) void k_abs_sum(const float *__restrict__ W, size_t n, unsigned long long *scratch)
+{
+    const float M = __uint_as_float((uint32_t)scratch[kSlotAbsMax]);
+    const int e = M > 0.0f ? ilogbf(M) : 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    unsigned long long s = 0;
+    for (; i < n; i += stride) {
+        const float w = W[i];
+        if (w == w) s += fix30(w, e);
+    }
+    s = wave_sum_u64(s);
+    if ((threadIdx.x & 63) == 0 && s) atomicAdd(&scratch[kSlotAbsSum], s);
+}
+
+// clipping search (Section 3.3): summed |W - d_k q| for the thresholds T_k = max|W| k / 32, k = 1..32
+__global__ __launch_bounds__(256) void k_clip_err(const float *__restrict__ W, size_t n, int bits,
+                                                  unsigned long long *scratch)
+{
+    const float M = __uint_as_float((uint32_t)scratch[kSlotAbsMax]);
+    if (M == 0.0f) return;
+    const int e = ilogbf(M);
+    const int qmax = (1 << (bits - 1)) - 1, qmin = -(1 << (bits - 1));
+    const float qm = (float)(qmax > 0 ? qmax : 1);
+    unsigned long long acc[kClipSteps];
 #pragma unroll
-    for (int i = 0; i < PB_MAX_BITS; ++i) wd[i] = 0;
-    if (r >= 0 && r < rows && w < cw) {
-        float d = grid_step(__uint_as_float(*absmax_slot), bits);
-        const float *src = W + (size_t)r * (size_t)cols;
-        for (int b = 0; b < 32; ++b) {
-            int c = w * 32 + b;
-            if (c >= cols) break;
-            uint32_t u = (uint32_t)quantize_code(src[c], d, bits);
+    for (int k = 0; k < kClipSteps; ++k) acc[k] = 0;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) {
+        const float w = W[i];
+        if (w != w) continue;
 #pragma unroll
-            for (int i = 0; i < PB_MAX_BITS; ++i)
-                if (i < bits) wd[i] |= ((u >> (bits - 1 - i)) & 1u) << b;
+        for (int k = 0; k < kClipSteps; ++k) {
+            const float d = __fdiv_rn(__fmul_rn(M, __fmul_rn((float)(k + 1), 0.03125f)), qm);
+            const float p = __fmul_rn(d, (float)quantize_code(w, d, qmin, qmax));
+            acc[k] += fix30(__fsub_rn(w, p), e);
         }
     }
 #pragma unroll
-    for (int i = 0; i < PB_MAX_BITS; ++i)
-        if (i < bits) packed[word_index(layout, cwp, layer_words, i, pr, w)] = wd[i];
+    for (int k = 0; k < kClipSteps; ++k) {
+        const unsigned long long s = wave_sum_u64(acc[k]);
+        if ((threadIdx.x & 63) == 0 && s) atomicAdd(&scratch[kSlotClip + k], s);
+    }
 }
 
-// reads max|W| from scales[0] (where k_absmax left it) and writes the layer scales
+// the step d of the chosen quantizer, left in scales[0] for the packing kernel
+__global__ void k_step(const unsigned long long *scratch, int bits, int quantizer, size_t n, float *scales)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0) return;
+    const float M = __uint_as_float((uint32_t)scratch[kSlotAbsMax]);
+    const int qmax = (1 << (bits - 1)) - 1;
+    const float qm = (float)(qmax > 0 ? qmax : 1);
+    float d;
+    if (quantizer == PB_QUANT_RANGE) {
+        const float hi = from_ordered_key((uint32_t)scratch[kSlotMax]), lo = from_ordered_key((uint32_t)scratch[kSlotMin]);
+        d = (scratch[kSlotMax] != 0 && hi > lo) ? __fdiv_rn(__fsub_rn(hi, lo), (float)(1 << (bits - 1))) : 1.0f;
+    } else if (quantizer == PB_QUANT_SIGN) {
+        const int e = M > 0.0f ? ilogbf(M) : 0;
+        d = (float)(ldexp((double)scratch[kSlotAbsSum], e - 30) / (double)n);
+    } else if (quantizer == PB_QUANT_CLIP_SEARCH && M != 0.0f) {
+        int best = kClipSteps;
+        unsigned long long best_err = scratch[kSlotClip + kClipSteps - 1];
+        for (int k = kClipSteps - 1; k >= 1; --k)
+            if (scratch[kSlotClip + k - 1] < best_err) { best = k; best_err = scratch[kSlotClip + k - 1]; }
+        d = __fdiv_rn(__fmul_rn(M, __fmul_rn((float)best, 0.03125f)), qm);
+    } else {
+        d = (M == 0.0f) ? 1.0f : __fdiv_rn(M, qm);
+    }
+    scales[0] = d;
+}
+
+// One wave per (packed row, 64 columns): a lane quantizes one weight (a coalesced 256-byte read), the ballot of
+// bit B-1-i over the wave IS two packed words of bitlayer i; lane i keeps and stores them (8 bytes).
+__global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint32_t layout, int rows, int cols,
+                                              int bits, int cwp, int rows_p, int gate_h, size_t layer_words,
+                                              int quantizer, const float *__restrict__ step,
+                                              uint32_t *__restrict__ packed)
+{
+    const int lane = threadIdx.x & 63;
+    const int groups = cwp / 2;
+    const long long tasks = (long long)rows_p * groups;
+    const long long wave0 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const long long nwaves = ((long long)gridDim.x * blockDim.x) >> 6;
+    const float d = *step;
+    const int qmax = (1 << (bits - 1)) - 1, qmin = -(1 << (bits - 1));
+    for (long long task = wave0; task < tasks; task += nwaves) {
+        const int pr = (int)(task / groups), g = (int)(task % groups);
+        const int r = gate_h ? gates_matrix_row(pr, gate_h) : pr;   // matrix row (-1 or >= rows: padding)
+        const int c = 64 * g + lane;
+        uint32_t u = 0;
+        if (r >= 0 && r < rows && c < cols) {
+            const float w = W[(size_t)r * (size_t)cols + c];
+            u = (uint32_t)(quantizer == PB_QUANT_SIGN ? ((w >= 0.0f || w != w) ? 1 : -1) : quantize_code(w, d, qmin, qmax));
+        }
+        uint32_t lo = 0, hi = 0;
+        for (int i = 0; i < bits; ++i) {
+            const unsigned long long bal = __ballot((u >> (bits - 1 - i)) & 1u);
+            lo = (lane == i) ? (uint32_t)bal : lo;
+            hi = (lane == i) ? (uint32_t)(bal >> 32) : hi;
+        }
+        if (lane < bits)
+            *reinterpret_cast<uint2 *>(packed + word_index(layout, cwp, layer_words, lane, pr, 2 * g)) = make_uint2(lo, hi);
+    }
+}
+
+// reads the step from scales[0] (where k_step left it) and writes the layer scales
 __global__ void k_scales(float *scales, int bits)
 {
     if (blockIdx.x != 0 || threadIdx.x != 0) return;
-    float d = grid_step(scales[0], bits);
+    const float d = scales[0];
     for (int i = 0; i < bits; ++i) {
         float v = d * ldexpf(1.0f, bits - 1 - i);
         scales[i] = (i == 0) ? -v : v;
@@ -113,18 +223,25 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
     q[idx] = v;
 }
 
-int launch_quantize_pack(const float *W, const Layout &L, uint32_t *packed, float *scales, hipStream_t st)
+int launch_quantize_pack(const float *W, const Layout &L, int quantizer, uint32_t *packed, float *scales,
+                         hipStream_t st)
 {
-    size_t n = (size_t)L.rows * (size_t)L.cols;
-    uint32_t *slot = reinterpret_cast<uint32_t *>(scales);
-    hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, slot, (size_t)1, 0u);
+    const size_t n = (size_t)L.rows * (size_t)L.cols;
+    unsigned long long *scratch = reinterpret_cast<unsigned long long *>(packed);
+    hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(kScratchWords), 0, st, scratch, (int)kScratchWords, 0ull);
     int blocks = (int)((n + 256 * 16 - 1) / (256 * 16));
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(k_absmax, dim3(blocks), dim3(256), 0, st, W, n, slot);
-    size_t total = L.layer_words;
-    hipLaunchKernelGGL(k_pack, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st, W, L.layout, L.rows, L.cols,
-                       L.bits, L.cw, L.cwp, L.rows_p, L.gate_h, L.layer_words, slot, packed);
+    hipLaunchKernelGGL(k_stats, dim3(blocks), dim3(256), 0, st, W, n, scratch);
+    if (quantizer == PB_QUANT_SIGN) hipLaunchKernelGGL(k_abs_sum, dim3(blocks), dim3(256), 0, st, W, n, scratch);
+    if (quantizer == PB_QUANT_CLIP_SEARCH)
+        hipLaunchKernelGGL(k_clip_err, dim3(blocks), dim3(256), 0, st, W, n, L.bits, scratch);
+    hipLaunchKernelGGL(k_step, dim3(1), dim3(64), 0, st, scratch, L.bits, quantizer, n, scales);
+    const long long tasks = (long long)L.rows_p * (L.cwp / 2);
+    long long pblocks = (tasks + 3) / 4;            // four waves per block, one task per wave and pass
+    if (pblocks > 16384) pblocks = 16384;
+    hipLaunchKernelGGL(k_pack, dim3((unsigned)pblocks), dim3(256), 0, st, W, L.layout, L.rows, L.cols, L.bits, L.cwp,
+                       L.rows_p, L.gate_h, L.layer_words, quantizer, scales, packed);
     hipLaunchKernelGGL(k_scales, dim3(1), dim3(64), 0, st, scales, L.bits);
     return (int)hipGetLastError();
 }

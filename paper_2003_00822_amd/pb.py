@@ -23,9 +23,10 @@ PB_LAYOUT_ROWMAJOR_V1 = 0x50420001   # AND + popcount kernel
 PB_LAYOUT_TILE16_V1 = 0x50420002     # matrix-core kernel (the default up to 16384 columns)
 PB_LAYOUT_TILE16_GATES_V1 = 0x50420003   # the same with the four gate rows of an LSTM unit in one row tile
 PB_ACT_NONE, PB_ACT_RELU = 0, 1
+PB_QUANT_SYMMETRIC, PB_QUANT_RANGE, PB_QUANT_SIGN, PB_QUANT_CLIP_SEARCH = 0, 1, 2, 3
 
 EXPORTS = [
-    "pb_desc_init", "pb_desc_init_layout", "pb_quantize_pack_desc", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
+    "pb_desc_init", "pb_desc_init_layout", "pb_quantize_pack_desc", "pb_quantize_pack_mode", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
     "pb_matmul_bias_act", "pb_matmul_acc", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
 ]
 
@@ -62,6 +63,8 @@ def lib():
         L.pb_desc_init_layout.restype = _I
         L.pb_quantize_pack_desc.argtypes = [_P, _D, _P, _P, _P]
         L.pb_quantize_pack_desc.restype = _I
+        L.pb_quantize_pack_mode.argtypes = [_P, _D, _I, _P, _P, _P]
+        L.pb_quantize_pack_mode.restype = _I
         L.pb_packed_bytes.argtypes = [_D]
         L.pb_packed_bytes.restype = ctypes.c_size_t
         L.pb_workspace_bytes.argtypes = [_D, _I]
@@ -165,6 +168,12 @@ def pb_quantize_pack_desc(W, d, packed, scales, stream=None):
                                        _stream(stream)), "pb_quantize_pack_desc")
 
 
+def pb_quantize_pack_mode(W, d, quantizer, packed, scales, stream=None):
+    _check(lib().pb_quantize_pack_mode(_ptr(W, torch.float32, "W"), ctypes.byref(d), quantizer,
+                                       _ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float32, "scales"),
+                                       _stream(stream)), "pb_quantize_pack_mode")
+
+
 def pb_unpack(packed, d, q, stream=None):
     _check(lib().pb_unpack(_ptr(packed, torch.uint8, "packed"), ctypes.byref(d), _ptr(q, torch.int32, "q"),
                            _stream(stream)), "pb_unpack")
@@ -222,7 +231,7 @@ class PackedLinear:
     """Convenience holder: one quantized, packed weight matrix with its scales and a workspace."""
 
     def __init__(self, W: torch.Tensor, bits: int, max_batch: int = 1, frac_bits: int = 16, act_bits: int = 32,
-                 layout: int | None = None):
+                 layout: int | None = None, quantizer: int = PB_QUANT_SYMMETRIC):
         assert W.is_cuda and W.dtype == torch.float32 and W.dim() == 2
         W = W.contiguous()
         self.rows, self.cols = W.shape
@@ -235,7 +244,7 @@ class PackedLinear:
         self.scales = torch.empty(max(bits, 4), dtype=torch.float32, device=W.device)
         self.max_batch = max_batch
         self.workspace = alloc_workspace(self.desc, max_batch, W.device)
-        pb_quantize_pack_desc(W, self.desc, self.packed, self.scales)
+        pb_quantize_pack_mode(W, self.desc, quantizer, self.packed, self.scales)
 
     def __call__(self, X: torch.Tensor, bits_used: int | None = None, out: torch.Tensor | None = None):
         X = X.reshape(-1, self.cols)

@@ -226,6 +226,43 @@ def test_extra_16384(pb, layout):
 GATES = 0x50420003
 
 
+@pytest.mark.parametrize("mode,bits", [(1, 1), (1, 3), (1, 8), (2, 2), (3, 1), (3, 2), (3, 4), (3, 8)])
+def test_quantizer_variants_match_the_oracle(pb, layout, mode, bits):
+    """Section 3.3's other quantizers: codes and scales bit-exact, then the product on top of them."""
+    rng = np.random.default_rng(100 * mode + bits)
+    for (R, C) in [(37, 200), (300, 1000)]:
+        W = rng.normal(0, 0.05, size=(R, C)).astype(np.float32)
+        W[3, 5] = 0.9                                  # an outlier, so that the clipping search clips
+        if mode == 1:
+            W += np.float32(0.02)                      # not symmetric: max - min differs from 2 max|W|
+        X = rng.normal(size=(2, C)).astype(np.float32)
+        prep = po.prepare(W, bits, mode)
+        lin = pb.PackedLinear(dev(W), bits, max_batch=2, layout=layout, quantizer=mode)
+        assert (lin.unpack().cpu().numpy() == prep["q"]).all(), (mode, bits, R, C)
+        assert (lin.scales[:bits].cpu().numpy().view(np.int32) == prep["scales"].view(np.int32)).all()
+        lw = po.pack_words(prep["layers"])
+        A_ref, Y_ref = po.matmul_words(lw, prep["scales"], bits, C, X)
+        assert (lin.acc(dev(X), bits).cpu().numpy() == A_ref).all()
+        assert_y_close(lin(dev(X), bits).cpu().numpy(), Y_ref, A_ref, prep["scales"])
+
+
+def test_quantizer_mode_arguments(pb):
+    d = pb.pb_desc_init(8, 64, 3)
+    W = torch.zeros((8, 64), device="cuda")
+    packed = pb.alloc_packed(d)
+    sc = torch.zeros(4, device="cuda")
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_quantize_pack_mode(W, d, 2, packed, sc)          # the +-1 code needs bits = 2
+    assert e.value.status == pb.PB_EINVAL
+    with pytest.raises(pb.PbError) as e:
+        pb.pb_quantize_pack_mode(W, d, 7, packed, sc)
+    assert e.value.status == pb.PB_EINVAL
+    # all-zero weights: step 1 (0 for the +-1 code), codes 0
+    for mode in (0, 1, 3):
+        pb.pb_quantize_pack_mode(W, d, mode, packed, sc)
+        assert sc[:3].cpu().tolist() == [-4.0, 2.0, 1.0]
+
+
 @pytest.mark.parametrize("H,I,batch", [(5, 3, 1), (37, 100, 2), (64, 64, 4), (1500, 1500, 1)])
 def test_gate_interleaved_layout_is_transparent(pb, H, I, batch):
     """The LSTM layout stores rows gate-interleaved; codes, accumulators and outputs come back in matrix order."""
