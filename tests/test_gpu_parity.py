@@ -205,6 +205,26 @@ def test_config5_large_fc_batch(pb, layout):
     run_layer(pb, W16, 8, X16, [8], layout=layout)
 
 
+def test_config5_full_size_batch_64_sampled_rows(pb, layout):
+    """Config 5 at its largest: 8192 x 8192, B = 8, batch 64, in the launch configuration the benchmark times;
+    the oracle computes sampled rows (all 64 vectors, all bitlayers) one by one."""
+    W, X = synth.fc_large(batch=64)
+    bits = 8
+    lin = pb.PackedLinear(dev(W), bits, max_batch=64, layout=layout)
+    rng = np.random.default_rng(5)
+    rows = sorted(set(rng.choice(8192, size=20, replace=False).tolist() + [0, 15, 16, 8191]))
+    Xd = dev(X)
+    A_gpu = lin.acc(Xd, bits).cpu().numpy()
+    Y_gpu = lin(Xd, bits).cpu().numpy()
+    prep = po.prepare(W, bits)
+    xq = po.fixed_point(X)
+    for r in rows:
+        sub = po.layer_products_direct(prep["layers"][:, r:r + 1, :], bits, xq)      # [bits, 64, 1]
+        assert (A_gpu[:, :, r] == sub[:, :, 0]).all(), r
+        y = po.dequant(sub[:, :, 0], prep["scales"], bits)
+        assert_y_close(Y_gpu[:, r], y, sub[:, :, 0], prep["scales"])
+
+
 def test_extra_16384(pb, layout):
     W, X = synth.fc_square(16384, 0.01, cfg=6)
     bits = 2
