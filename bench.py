@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--no-batch", action="store_true", help="skip the batched (8192 x 8192, batch 1..64) comparison")
     ap.add_argument("--no-sizes", action="store_true", help="skip the larger layers (8192, 16384: bandwidth asymptote)")
     ap.add_argument("--no-models", action="store_true", help="skip the MLP forward and the 35-step LSTM sequence")
+    ap.add_argument("--sweep-only", action="store_true",
+                    help="only the bits_used sweep of the headline workload (the run the profiler summaries are made "
+                         "from: every launch of the product kernel then belongs to the sweep)")
     ap.add_argument("--calib", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
@@ -247,6 +250,12 @@ def main():
         "roofline_other": other,
     }
 
+    if args.sweep_only:
+        if args.detail:
+            with open(args.detail, "w") as f:
+                json.dump(out, f, indent=1)
+        print(json.dumps(out), flush=True)
+        return
     out["same_gpu_references"] = same_gpu_references(torch, dev, W, X, per_m)
     if mfma:
         out["table1_analog"] = table1_analog(torch, pb, dev, W, X, out["same_gpu_references"]["fp32_matvec_us"])
@@ -299,7 +308,7 @@ def table1_analog(torch, pb, dev, W, X, fp32_us):
                          "speedup_vs_fp32": round(fp32_us / (t * 1e6), 2), "bound": round(32.0 / B, 2)})
             del pool, lin
     torch.cuda.empty_cache()
-    return {"workload": "FC 4096x4096, batch 1, bits_used = bitlayers", "fp32_matvec_us": fp32_us, "rows": rows}
+    return {"workload": "FC %dx%d, batch 1, bits_used = bitlayers" % (n, n), "fp32_matvec_us": fp32_us, "rows": rows}
 
 
 def same_gpu_references(torch, dev, W, X, per_m):
