@@ -1,31 +1,36 @@
 // The hot kernel on the matrix cores: the whole inference path of Algorithm 2 of the
 // paper in one launch -- x_q = Int(x * 2^f), the bitwise transpose into bit planes
-// (Section 3.4), the 1-bit products of Section 3.1 with the 32 planes of a vector
+// (Section 3.4), the 1-bit products of Section 3.1 with the planes of a vector
 // batched as the second matrix operand ("one batched matrix product"), the plane
 // weights [-2^31, 2^30 .. 2^0] and the scale-accumulation over the first `bits_used`
 // bitlayers (the run-time knob of the abstract).
 //
 // Why the matrix cores: AND + popcount costs two vector-ALU lane operations per
 // (32-bit weight word, plane); with 32 planes that is four times what the ALUs of
-// this chip can do while HBM delivers the words.  The same 0/1 inner products are
-// a dense contraction with N = 32 planes, and V_MFMA_SCALE_F32_16X16X128_F8F6F4 on
-// FP4 (E2M1) operands does 32768 of them per instruction with exact results: the
-// products are 0 or 1 and the fp32 accumulators count to 2^24.
+// this chip can do while HBM delivers the words.  The same inner products are a
+// dense contraction, and V_MFMA_SCALE_F32_16X16X128_F8F6F4 on FP4 (E2M1) operands
+// does 32768 multiply-adds per instruction with exact results.
 //
-// Operands.  A (16 x 128) = 16 planes x 128 columns, B (128 x 16) = 128 columns x
+// Two planes per operand row.  E2M1 holds 0, 0.5, 1.0 and 1.5 as the codes 0, 1, 2, 3,
+// so the two adjacent planes 2 i and 2 i + 1 of the activations travel as ONE row of
+// base-4 digits d = b_(2i) + 2 b_(2i+1) (FP4 code = d, value d / 2): the 32 planes of a
+// vector are the 16 rows of one A operand and the plane weights become 4^i.  The weight
+// bit is the code 2.0, so every product is the digit itself (0 .. 3), the fp32
+// accumulators hold integers below 2^24 and every sum is exact.
+// The sign plane: the digits are those of the offset value x' = x_q + 2^31 (top bit
+// flipped, all 16 digits unsigned), and A = sum w x' - 2^31 * popcount(w): the popcount
+// of the weight words of a block is four ALU operations per lane.
+//
+// Operands.  A (16 x 128) = 16 digit rows x 128 columns, B (128 x 16) = 128 columns x
 // 16 weight rows, D (16 x 16): lane l of D holds row j = l % 16 of the weights and
-// the planes 4 * (l / 16) + v in its four registers v, so the plane weighting is
-// arithmetic inside a lane.  Two instructions (planes 0-15 and 16-31) share one B.
-// A lane's B operand is 32 columns of one weight row = ONE packed word, expanded
-// from 1 bit to the 4-bit FP4 code per column with five ALU operations:
-//     b0 = w & 0x11111111 (0.5)   b1 = w & 0x22222222 (1.0)
-//     b2 = w & 0x44444444 (2.0)   b3 = (w >> 1) & 0x44444444 (2.0)
-// and the plane operand carries the matching codes 2.0, 1.0, 0.5, 0.5 so that every
-// product of two set bits is exactly 1.0.  Which column sits in which k slot does
-// not matter as long as both operands agree.
+// the digits 4 * (l / 16) + c in its four registers c, so the digit weighting is
+// arithmetic inside a lane.  A lane's B operand is 32 columns of one weight row = ONE
+// packed word; register r, nibble n of both operands is column 4 n + r of the word:
+//     b0 = (w << 2) & 0x44444444   b1 = (w << 1) & 0x44444444
+//     b2 = w & 0x44444444          b3 = (w >> 1) & 0x44444444
 //
 // Mapping.  A wave owns a slice of the columns (NQ chunks of 512) for its whole life
-// and keeps the expanded planes of that slice in registers; it streams the 1 KB
+// and keeps the digit rows of that slice in registers; it streams the 1 KB
 // blocks of its slice (see pb_layout.h) for row tile after row tile and bitlayer
 // after bitlayer with 16-byte loads, several blocks in flight.  The waves of a
 // workgroup are the slices of one row; their per-(row, bitlayer) sums meet in LDS
@@ -114,22 +119,23 @@ __device__ __forceinline__ double row_sum16(double z)
     return z;
 }
 
-// Per-lane constants of the 16 x 16 bit-matrix transpose across a row of 16 lanes (both 16-bit halves of a
-// register at once): in stage J lanes l and l ^ J exchange the bit positions that have bit J set (lower lane)
-// / clear (upper lane); keep = the positions a lane keeps, rot = right-rotation that moves the partner's bits
-// into the others (>> J for the upper lane, << J for the lower).
+// Per-lane constants of the 16 x 16 transpose of 2-bit digits across a row of 16 lanes: lane L enters with the 32-bit
+// value of one column, lane i leaves with digit i (bits 2 i, 2 i + 1) of the 16 columns, the digit of the column
+// that entered in lane L at bits 2 L, 2 L + 1.  In stage J lanes l and l ^ J exchange the digit positions that have
+// bit J set (lower lane) / clear (upper lane); keep = the positions a lane keeps, rot = right-rotation that moves
+// the partner's digits into the others (>> 2 J for the upper lane, << 2 J for the lower).
 struct TransposeConsts {
     uint32_t keep8, keep4, keep2, keep1;
-    uint32_t rot8, rot4, rot2, rot1;
+    uint32_t rot4, rot2, rot1;
 };
 
 __device__ __forceinline__ TransposeConsts transpose_consts(int lane)
 {
     TransposeConsts c;
-    c.keep8 = (lane & 8) ? 0xFF00FF00u : 0x00FF00FFu; c.rot8 = (lane & 8) ? 8 : 24;
-    c.keep4 = (lane & 4) ? 0xF0F0F0F0u : 0x0F0F0F0Fu; c.rot4 = (lane & 4) ? 4 : 28;
-    c.keep2 = (lane & 2) ? 0xCCCCCCCCu : 0x33333333u; c.rot2 = (lane & 2) ? 2 : 30;
-    c.keep1 = (lane & 1) ? 0xAAAAAAAAu : 0x55555555u; c.rot1 = (lane & 1) ? 1 : 31;
+    c.keep8 = (lane & 8) ? 0xFFFF0000u : 0x0000FFFFu;
+    c.keep4 = (lane & 4) ? 0xFF00FF00u : 0x00FF00FFu; c.rot4 = (lane & 4) ? 8 : 24;
+    c.keep2 = (lane & 2) ? 0xF0F0F0F0u : 0x0F0F0F0Fu; c.rot2 = (lane & 2) ? 4 : 28;
+    c.keep1 = (lane & 1) ? 0xCCCCCCCCu : 0x33333333u; c.rot1 = (lane & 1) ? 2 : 30;
     return c;
 }
 
@@ -141,24 +147,44 @@ __device__ __forceinline__ uint32_t transpose_stage(uint32_t x, uint32_t keep, u
     return (x & keep) | (moved & ~keep);
 }
 
-// Lane r of a row holds, in each 16-bit half, 16 bits of one column; returns, in lane r, bit r of the 16 columns
-// of the row (for each half).
-__device__ __forceinline__ uint32_t bit_transpose16(uint32_t x, const TransposeConsts &c)
+__device__ __forceinline__ uint32_t digit_transpose16(uint32_t x, const TransposeConsts &c)
 {
-    x = transpose_stage<8>(x, c.keep8, c.rot8);
+    x = transpose_stage<8>(x, c.keep8, 16);
     x = transpose_stage<4>(x, c.keep4, c.rot4);
     x = transpose_stage<2>(x, c.keep2, c.rot2);
     x = transpose_stage<1>(x, c.keep1, c.rot1);
     return x;
 }
 
-// Plane word -> the four A-operand registers (FP4 codes 2.0, 1.0, 0.5, 0.5 facing the weight codes 0.5, 1.0, 2.0, 2.0)
-__device__ __forceinline__ void expand_plane(uint32_t pw, u32x4 &dst)
+// The column that lane L of a row converts, among the 16 of its half word: with this order the transposed word has
+// the digit of column 4 n + r (of the half word) at bits 4 n + 2 (r & 1) + 16 (r >> 1), which the A operand needs
+// at bits 4 n of register r.
+__device__ __forceinline__ int lane_column(int L)
 {
-    dst.x = (pw & 0x11111111u) << 2;
-    dst.y = pw & 0x22222222u;
-    dst.z = (pw & 0x44444444u) >> 2;
-    dst.w = (pw >> 3) & 0x11111111u;
+    return (L & 1) | ((L >> 2) & 2) | ((L << 1) & 4) | ((L << 1) & 8);
+}
+
+// Transposed digits of the two half words (columns 0-15, 16-31) -> the four A-operand registers
+// (register r, nibble n = digit of column 4 n + r, FP4 code = the digit)
+__device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, u32x4 &dst)
+{
+    const uint32_t m0 = __builtin_amdgcn_perm(q, p, 0x05040100u);   // low halves of p and q
+    const uint32_t m1 = __builtin_amdgcn_perm(q, p, 0x07060302u);   // high halves
+    dst.x = m0 & 0x33333333u;
+    dst.y = (m0 >> 2) & 0x33333333u;
+    dst.z = m1 & 0x33333333u;
+    dst.w = (m1 >> 2) & 0x33333333u;
+}
+
+// The same operand from the two plane words (bit c = column c) of a digit row
+__device__ __forceinline__ void digit_operand_from_planes(uint32_t p0, uint32_t p1, u32x4 &dst)
+{
+    const uint32_t e = (p0 & 0x55555555u) | ((p1 & 0x55555555u) << 1);   // columns 4 n (bits 4 n) and 4 n + 2
+    const uint32_t o = ((p0 >> 1) & 0x55555555u) | (p1 & 0xAAAAAAAAu);   // columns 4 n + 1 and 4 n + 3
+    dst.x = e & 0x33333333u;
+    dst.y = o & 0x33333333u;
+    dst.z = (e >> 2) & 0x33333333u;
+    dst.w = (o >> 2) & 0x33333333u;
 }
 
 __device__ __forceinline__ v8i as_operand(const u32x4 v)
@@ -167,9 +193,10 @@ __device__ __forceinline__ v8i as_operand(const u32x4 v)
     return r;
 }
 
+// One packed word -> the B operand: FP4 code 2.0 where the weight bit is set
 __device__ __forceinline__ v8i weight_operand(uint32_t w)
 {
-    v8i r = {(int)(w & 0x11111111u), (int)(w & 0x22222222u), (int)(w & 0x44444444u),
+    v8i r = {(int)((w << 2) & 0x44444444u), (int)((w << 1) & 0x44444444u), (int)(w & 0x44444444u),
              (int)((w >> 1) & 0x44444444u), 0, 0, 0, 0};
     return r;
 }
@@ -180,25 +207,23 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
     return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, 0x7F, 0, 0x7F);
 }
 
-// NQ: chunks of 512 columns per wave; NV: activation vectors whose planes a wave keeps (each weight block is
+// NQ: chunks of 512 columns per wave; NV: activation vectors whose digit rows a wave keeps (each weight block is
 // expanded once and multiplied with all of them); MAXS: most waves (column slices) per workgroup, which bounds
 // the registers a wave may use; RU: units (row tile, bitlayer) whose blocks a wave has in flight.  The host picks
 // RU <= the units a wave has, so that a short stream pays for no empty ring slots; 4 KB in flight per wave
 // measured best (more requests in flight than that slow the short streams down and do not speed up the long ones).
-// HI: planes 16-31 are computed.  Activations of at most 16 bits (Section 3.1: k = 8, 16) have planes 15-31 all
-// equal to their sign plane, which together weigh -2^15: one matrix instruction per step instead of two, half the
-// transpose, same integers.
-template <int NQ, int NV, int MAXS, int RU, bool HI>
+template <int NQ, int NV, int MAXS, int RU>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 {
     // Units requested before the activations have arrived (a head start that keeps HBM busy during the transpose);
-    // the rest of the ring follows once the planes are built.
+    // the rest of the ring follows once the digit rows are built.
 #ifndef PB_MFMA_PRE
 #define PB_MFMA_PRE 2
 #endif
     constexpr int PRE = NQ >= 4 ? (PB_MFMA_PRE < 1 ? PB_MFMA_PRE : 1) : (RU < PB_MFMA_PRE ? RU : PB_MFMA_PRE);
-    // (low 16 planes, high 16 planes) sums per vector, bitlayer and row; two buffers, used by alternate row tiles
-    __shared__ int2 abuf[2][NV][PB_MAX_BITS][kTileRows];
+    // sums per vector, bitlayer, half (digits 0-7 in units of 1, digits 8-15 in units of 2^16) and row; two buffers,
+    // used by alternate row tiles
+    __shared__ int abuf[2][NV][PB_MAX_BITS][2][kTileRows];
     __shared__ float s_scales[PB_MAX_BITS];
 
     const int lane = threadIdx.x & 63;
@@ -213,7 +238,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int U = rounds * m;
 
     // layer scales, lane i holds scales[i]: the oldest load of the wave, so that no later wait is held up by it;
-    // parked in LDS once the planes are built (the barrier before the first final sum orders that store)
+    // parked in LDS once the digit rows are built (the barrier before the first final sum orders that store)
     const float scv = (a.scales && lane < m) ? a.scales[lane] : 0.0f;
 
     // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
@@ -244,178 +269,180 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     // and before any wave requests weights: the memory pipeline of a CU returns data in request order, so an
     // activation load queued behind another wave's weight loads (HBM misses) would arrive a memory latency late.
     auto zero_sums_and_meet = [&]() {
-        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * kTileRows; i += blockDim.x)
-            (&abuf[0][0][0][0])[i] = make_int2(0, 0);
+        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * 2 * kTileRows; i += blockDim.x)
+            (&abuf[0][0][0][0][0])[i] = 0;
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // ---- the planes of this wave's slice, expanded to A operands, kept in registers ----
-    // lane l = 16 * kb + p: planes p (lo) and 16 + p (hi) of the words 16 * q + 4 * kb + t
+    // ---- the digit rows of this wave's slice, as A operands, kept in registers ----
+    // lane l = 16 * kb + i: digit i (planes 2 i, 2 i + 1 of x' = x_q ^ 2^31) of the words 16 * q + 4 * kb + t
     const int kb = lane >> 4;
-    u32x4 pa_lo[NV][NQ][4], pa_hi[NV][NQ][4];
+    u32x4 pa[NV][NQ][4];
+    constexpr int VG = NV > 4 ? 4 : NV;   // vectors whose activations are in flight together
     if (a.planes) {
-        uint4 plo[NV][NQ], phi[NV][NQ];
+        const uint32_t flip = (lane & 15) == 15 ? 0xFFFFFFFFu : 0u;   // plane 31 of x' is the complement of x_q's
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int n = min(n0 + v, a.batch - 1);
-            const bool live = n0 + v < a.batch;
-            const uint32_t *pl =
-                a.planes + ((size_t)n * 32 + (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
+        for (int g = 0; g < NV; g += VG) {
+            uint4 pl0[VG][NQ], pl1[VG][NQ];
 #pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-                plo[v][q] = phi[v][q] = make_uint4(0, 0, 0, 0);
-                if (q < nq && live) {
-                    plo[v][q] = *reinterpret_cast<const uint4 *>(pl + q * 16);
-                    phi[v][q] = *reinterpret_cast<const uint4 *>(pl + (size_t)16 * a.cwp + q * 16);
+            for (int v = 0; v < VG; ++v) {
+                const int n = min(n0 + g + v, a.batch - 1);
+                const bool live = n0 + g + v < a.batch;
+                const uint32_t *pl =
+                    a.planes + ((size_t)n * 32 + 2 * (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    pl0[v][q] = pl1[v][q] = make_uint4(0, 0, 0, 0);
+                    if (q < nq && live) {
+                        pl0[v][q] = *reinterpret_cast<const uint4 *>(pl + q * 16);
+                        pl1[v][q] = *reinterpret_cast<const uint4 *>(pl + (size_t)a.cwp + q * 16);
+                    }
                 }
             }
+            if (g == 0) {
+                zero_sums_and_meet();
+#pragma unroll
+                for (int k = 0; k < PRE; ++k) issue(ring[k]);
+            }
+#pragma unroll
+            for (int v = 0; v < VG; ++v)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q) {
+                    const uint4 p0 = pl0[v][q], p1 = pl1[v][q];
+                    digit_operand_from_planes(p0.x, p1.x ^ flip, pa[g + v][q][0]);
+                    digit_operand_from_planes(p0.y, p1.y ^ flip, pa[g + v][q][1]);
+                    digit_operand_from_planes(p0.z, p1.z ^ flip, pa[g + v][q][2]);
+                    digit_operand_from_planes(p0.w, p1.w ^ flip, pa[g + v][q][3]);
+                }
         }
-        zero_sums_and_meet();
-#pragma unroll
-        for (int k = 0; k < PRE; ++k) issue(ring[k]);
-#pragma unroll
-        for (int v = 0; v < NV; ++v)
-#pragma unroll
-            for (int q = 0; q < NQ; ++q) {
-                const uint4 lo = plo[v][q], hi = phi[v][q];
-                expand_plane(lo.x, pa_lo[v][q][0]); expand_plane(lo.y, pa_lo[v][q][1]);
-                expand_plane(lo.z, pa_lo[v][q][2]); expand_plane(lo.w, pa_lo[v][q][3]);
-                if (HI) {
-                    expand_plane(hi.x, pa_hi[v][q][0]); expand_plane(hi.y, pa_hi[v][q][1]);
-                    expand_plane(hi.z, pa_hi[v][q][2]); expand_plane(hi.w, pa_hi[v][q][3]);
-                }
-            }
     } else {
-        // Algorithm 2: x_q = Int(x * 2^f); then the bitwise transpose, 32 columns x 32 bits at a time in each
-        // half of the wave: lane (half H, column c) converts column c of word 16 q + 4 (2 H + e) + t, e = 0, 1.
+        // Algorithm 2: x_q = Int(x * 2^f); then the transpose, 32 columns x 16 digits at a time in each half of
+        // the wave: lane (half H, c) converts one column of the words 16 q + 4 (2 H + e) + t, e = 0, 1.
         // V_PERMLANE16_SWAP hands the even rows of 16 lanes both 16-column halves of the e = 0 word and the odd
-        // rows those of the e = 1 word, which is the first stage of the 32 x 32 transpose; the other four stages
-        // stay inside a row.  Lane (kb, p) ends with planes p and 16 + p of word 16 q + 4 kb + t.
+        // rows those of the e = 1 word; the four exchange stages stay inside a row.  Lane (kb, i) ends with digit
+        // i of the 32 columns of word 16 q + 4 kb + t.
         // Buffer loads return 0 beyond the end of a vector, and for the vectors beyond the end of the batch.
-        const int colb = (32 * (16 * q0 + 8 * (lane >> 5)) + (lane & 31)) * 4;   // byte offset of (q = 0, e = 0, t = 0)
-        uint32_t xv[NV][NQ][4][2];
-#pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const int n = min(n0 + v, a.batch - 1);
-            const bool live = n0 + v < a.batch;
-            const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
-                const_cast<float *>(a.X0 + (size_t)n * a.cols0), 0, live ? a.cols0 * 4 : 0, 0x00020000);
-#pragma unroll
-            for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                for (int t = 0; t < 4; ++t)
-#pragma unroll
-                    for (int e = 0; e < 2; ++e)
-                        xv[v][q][t][e] =
-                            __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
-        }
-        // Second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range.
-        // Columns of the first part would have negative offsets here; those are clamped and the value dropped
-        // (a negative register offset that an instruction offset brings back above zero is not range-checked
-        // lane by lane on this hardware).
-        uint32_t xw[NV][NQ][4][2];
+        const int colb = (32 * (16 * q0 + 8 * (lane >> 5)) + (lane & 16) + lane_column(lane & 15)) * 4;
         const int colb1 = colb - a.cols0 * 4;
-        if (a.X1) {
-#pragma unroll
-            for (int v = 0; v < NV; ++v) {
-                const int n = min(n0 + v, a.batch - 1);
-                const bool live = n0 + v < a.batch;
-                const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<float *>(a.X1 + (size_t)n * a.cols1), 0, live ? a.cols1 * 4 : 0, 0x00020000);
-#pragma unroll
-                for (int q = 0; q < NQ; ++q)
-#pragma unroll
-                    for (int t = 0; t < 4; ++t)
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            xw[v][q][t][e] = __builtin_amdgcn_raw_buffer_load_b32(
-                                rx1, max(colb1 + 128 * (16 * q + 4 * e + t), 0), 0, 0);
-            }
-        }
-        zero_sums_and_meet();
-#pragma unroll
-        for (int k = 0; k < PRE; ++k) issue(ring[k]);
         const TransposeConsts tc = transpose_consts(lane);
-        if (a.X1) {
 #pragma unroll
-            for (int v = 0; v < NV; ++v)
+        for (int g = 0; g < NV; g += VG) {
+            uint32_t xv[VG][NQ][4][2];
+#pragma unroll
+            for (int v = 0; v < VG; ++v) {
+                const int n = min(n0 + g + v, a.batch - 1);
+                const bool live = n0 + g + v < a.batch;
+                const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<float *>(a.X0 + (size_t)n * a.cols0), 0, live ? a.cols0 * 4 : 0, 0x00020000);
 #pragma unroll
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
                     for (int t = 0; t < 4; ++t)
 #pragma unroll
                         for (int e = 0; e < 2; ++e)
-                            xv[v][q][t][e] |= colb1 + 128 * (16 * q + 4 * e + t) >= 0 ? xw[v][q][t][e] : 0u;
-        }
+                            xv[v][q][t][e] =
+                                __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
+            }
+            // Second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range.
+            // Columns of the first part would have negative offsets here; those are clamped and the value dropped
+            // (a negative register offset that an instruction offset brings back above zero is not range-checked
+            // lane by lane on this hardware).
+            uint32_t xw[VG][NQ][4][2];
+            if (a.X1) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v)
+                for (int v = 0; v < VG; ++v) {
+                    const int n = min(n0 + g + v, a.batch - 1);
+                    const bool live = n0 + g + v < a.batch;
+                    const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
+                        const_cast<float *>(a.X1 + (size_t)n * a.cols1), 0, live ? a.cols1 * 4 : 0, 0x00020000);
 #pragma unroll
-            for (int q = 0; q < NQ; ++q)
+                    for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const uint32_t X =
-                        (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][0]), a.fscale, a.imin, a.imax);
-                    const uint32_t Y =
-                        (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][1]), a.fscale, a.imin, a.imax);
-                    const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
-                    // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
-                    const uint32_t c_lo = sw[0], c_hi = sw[1];
-                    const uint32_t lo = (c_lo & 0xFFFFu) | (c_hi << 16);         // bits 0-15 of the 32 columns
-                    const uint32_t hi = (c_hi & 0xFFFF0000u) | (c_lo >> 16);     // bits 16-31
-                    expand_plane(bit_transpose16(lo, tc), pa_lo[v][q][t]);
-                    if (HI) expand_plane(bit_transpose16(hi, tc), pa_hi[v][q][t]);
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int e = 0; e < 2; ++e)
+                                xw[v][q][t][e] = __builtin_amdgcn_raw_buffer_load_b32(
+                                    rx1, max(colb1 + 128 * (16 * q + 4 * e + t), 0), 0, 0);
                 }
+            }
+            if (g == 0) {
+                zero_sums_and_meet();
+#pragma unroll
+                for (int k = 0; k < PRE; ++k) issue(ring[k]);
+            }
+            if (a.X1) {
+#pragma unroll
+                for (int v = 0; v < VG; ++v)
+#pragma unroll
+                    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                        for (int t = 0; t < 4; ++t)
+#pragma unroll
+                            for (int e = 0; e < 2; ++e)
+                                xv[v][q][t][e] |= colb1 + 128 * (16 * q + 4 * e + t) >= 0 ? xw[v][q][t][e] : 0u;
+            }
+#pragma unroll
+            for (int v = 0; v < VG; ++v)
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                    for (int t = 0; t < 4; ++t) {
+                        // x' = x_q + 2^31 as an unsigned value: the top bit flipped
+                        const uint32_t X = 0x80000000u ^
+                            (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][0]), a.fscale, a.imin, a.imax);
+                        const uint32_t Y = 0x80000000u ^
+                            (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][1]), a.fscale, a.imin, a.imax);
+                        const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
+                        // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
+                        digit_operand(digit_transpose16(sw[0], tc), digit_transpose16(sw[1], tc), pa[g + v][q][t]);
+                    }
+        }
     }
     if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
-    // per-lane plane weights: registers c of the low / high instruction hold planes 4 kb + c / 16 + 4 kb + c
-    float kl[4], kh[4];
+    // per-lane digit weights: register c holds digit 4 kb + c, which weighs 4^(4 kb + c); lanes kb = 0, 1 sum
+    // digits 0-7 (bits 0-15 of x') in units of 1, lanes kb = 2, 3 digits 8-15 in units of 2^16
+    float kw[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) {
-        kl[c] = (float)(1 << (4 * kb + c));
-        kh[c] = (kb == 3 && c == 3) ? -kl[c] : kl[c];    // plane 31 weighs -2^31 (Algorithm 2)
-    }
-    if (!HI && kb == 3) kl[3] = -kl[3];                  // 16-bit activations: plane 15 stands for planes 15-31, -2^15
+    for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * c + 8 * (kb & 1)));
 
-    const int j = lane & 15;
+    const int j = lane & 15, half = lane >> 5;
     int pi = 0, pr = 0;   // bitlayer and round of the unit being multiplied
     for (int u0 = 0; u0 < U; u0 += RU) {
 #pragma unroll
         for (int k = 0; k < RU; ++k) {
             if (u0 + k < U) {
-                v4f acc_lo[NV], acc_hi[NV];
+                v4f acc[NV];
 #pragma unroll
-                for (int v = 0; v < NV; ++v) acc_lo[v] = acc_hi[v] = v4f{0.f, 0.f, 0.f, 0.f};
-                // (chunks beyond a ragged last slice multiply zero planes by zero weights)
+                for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                // (chunks beyond a ragged last slice multiply zero weights)
+                int pc = 0;   // set bits of this lane's weight words: row j, k-block kb
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     const u32x4 w = ring[k][q];
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
                         const v8i b = weight_operand(w[t]);
+                        pc += __builtin_popcount(w[t]);
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) {
-                            acc_lo[v] = mfma_fp4(as_operand(pa_lo[v][q][t]), b, acc_lo[v]);
-                            if (HI) acc_hi[v] = mfma_fp4(as_operand(pa_hi[v][q][t]), b, acc_hi[v]);
-                        }
+                        for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
                     }
                 }
-                // plane weighting inside the lane.  Counts are <= 2048 (a slice has at most 2048 columns), so
-                // c0 + 2 c1 + 4 c2 +- 8 c3 < 2^15 and its multiple by 2^(4 kb) is exact in fp32 and < 2^27.
+                // sum w x_q = sum w x' - 2^31 * popcount(w).  The lanes of the upper half (units of 2^16) subtract
+                // 2^15 times the popcount of their own k-block and of the one 32 lanes below.
+                const auto pcs = __builtin_amdgcn_permlane32_swap((uint32_t)pc, (uint32_t)pc, false, false);
+                const int corr = half ? (int)((pcs[0] + pcs[1]) << 15) : 0;
+                // digit weighting inside the lane.  Sums of digits are <= 3 * 2048 (a slice has at most 2048
+                // columns), so c0 + 4 c1 + 16 c2 + 64 c3 < 2^20 and its multiple by 2^8 is exact in fp32 and < 2^28.
 #pragma unroll
                 for (int v = 0; v < NV; ++v) {
-                    const float lo_f = acc_lo[v][0] * kl[0] + acc_lo[v][1] * kl[1] + acc_lo[v][2] * kl[2] +
-                                       acc_lo[v][3] * kl[3];
-                    const float hi_f = acc_hi[v][0] * kh[0] + acc_hi[v][1] * kh[1] + acc_hi[v][2] * kh[2] +
-                                       acc_hi[v][3] * kh[3];
-                    int2 *dst = &abuf[pr & 1][v][pi][j];
-                    atomicAdd(&dst->x, (int)lo_f);
-                    if (HI) atomicAdd(&dst->y, (int)hi_f);
+                    const float f = acc[v][0] * kw[0] + acc[v][1] * kw[1] + acc[v][2] * kw[2] + acc[v][3] * kw[3];
+                    atomicAdd(&abuf[pr & 1][v][pi][half][j], (int)f - corr);
                 }
                 if (++pi == m) {
                     // The row tile is complete in every slice: scale and store it.  (The barrier per row tile also
@@ -432,21 +459,21 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         const int prow = (rt0 + pr) * kTileRows + jrow;
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
                         const bool live = n < a.batch && row >= 0 && row < a.R;
-                        int2 s = make_int2(0, 0);
+                        int s_lo = 0, s_hi = 0;
                         if (il < m) {
-                            int2 *src = &abuf[pr & 1][v][il][jrow];
-                            s = *src;
-                            *src = make_int2(0, 0);
+                            int *src = &abuf[pr & 1][v][il][0][jrow];
+                            s_lo = src[0];
+                            s_hi = src[kTileRows];
+                            src[0] = 0;
+                            src[kTileRows] = 0;
                         }
-                        // A_i = lo + hi * 2^16 exactly: 0 <= lo < 2^31 (unsigned), |hi| <= 2^30; with 16 planes lo
-                        // carries the sign plane itself, |lo| < 2^30, and hi is 0
-                        const long long lo = HI ? (long long)(uint32_t)s.x : (long long)s.x;
+                        // A_i = lo + hi * 2^16 exactly: 0 <= lo < 2^30, |hi| < 2^30
+                        const long long Ai = (long long)s_lo + ((long long)s_hi << 16);
                         if (a.A) {
-                            if (live && il < m)
-                                a.A[((size_t)il * a.batch + n) * (size_t)a.R + row] = lo + ((long long)s.y << 16);
+                            if (live && il < m) a.A[((size_t)il * a.batch + n) * (size_t)a.R + row] = Ai;
                             continue;
                         }
-                        const double z = row_sum16((double)s_scales[il] * ((double)lo + (double)s.y * 65536.0));
+                        const double z = row_sum16((double)s_scales[il] * (double)Ai);
                         float y = (float)(z * a.out_scale);
                         if (a.bias && live) y += a.bias[row];
                         if (a.c_prev) {
@@ -476,18 +503,19 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 // The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup, ring depth in units).
 struct Variant {
     int nq, nv, maxs, ru;
-    const void *fn, *fn16;    // 32 planes, 16 planes
+    const void *fn;
 };
-#define PB_VARIANT(NQ, NV, MAXS, RU)                                                          \
-    {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true>),        \
-     reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false>)}
+#define PB_VARIANT(NQ, NV, MAXS, RU) {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU>)}
 static const Variant kVariants[] = {
     PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
-    PB_VARIANT(1, 2, 8, 1),  PB_VARIANT(1, 2, 8, 2),  PB_VARIANT(1, 2, 8, 4),
+    PB_VARIANT(1, 2, 16, 1), PB_VARIANT(1, 2, 16, 2), PB_VARIANT(1, 2, 16, 4),
     PB_VARIANT(1, 4, 8, 1),  PB_VARIANT(1, 4, 8, 2),  PB_VARIANT(1, 4, 8, 4),
+    PB_VARIANT(1, 8, 8, 1),  PB_VARIANT(1, 8, 8, 2),  PB_VARIANT(1, 8, 8, 4),
     PB_VARIANT(2, 1, 16, 1), PB_VARIANT(2, 1, 16, 2),
     PB_VARIANT(2, 2, 8, 1),  PB_VARIANT(2, 2, 8, 2),
+    PB_VARIANT(2, 4, 8, 1),  PB_VARIANT(2, 4, 8, 2),
     PB_VARIANT(4, 1, 8, 1),  PB_VARIANT(4, 1, 8, 2),
+    PB_VARIANT(4, 2, 8, 1),  PB_VARIANT(4, 2, 8, 2),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
@@ -579,7 +607,7 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
     void *args[] = {&a};
     const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * bits_used)];
-    const hipError_t e = hipLaunchKernel(act_bits > 16 ? run.fn : run.fn16, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
+    const hipError_t e = hipLaunchKernel(run.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
                                          0, st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
 }
