@@ -89,13 +89,6 @@ __device__ __forceinline__ uint32_t dpp_mov(uint32_t v)
 }
 
 // value of lane (l ^ J) for J < 16, inside each row of 16 lanes, on the vector ALU alone (DPP modifiers)
-// value of lane L of the wave (a scalar)
-template <int L>
-__device__ __forceinline__ float lane_value(float v)
-{
-    return __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(v), L));
-}
-
 template <int J>
 __device__ __forceinline__ uint32_t row_xor(uint32_t v)
 {
@@ -105,18 +98,19 @@ __device__ __forceinline__ uint32_t row_xor(uint32_t v)
     else return dpp_mov<0xB1>(v);                                       // quad_perm [1,0,3,2]
 }
 
-// sum over the 16 lanes of a row, in every lane (xor butterfly on the vector ALU)
-__device__ __forceinline__ double row_sum16(double z)
+// z + (z of the lane D lanes away, D = 16 or 32), in both lanes
+template <int D>
+__device__ __forceinline__ double add_across(double z)
 {
-#define PB_STEP(J)                                                                                  \
-    {                                                                                               \
-        const unsigned long long b = (unsigned long long)__double_as_longlong(z);                   \
-        const uint32_t lo = row_xor<J>((uint32_t)b), hi = row_xor<J>((uint32_t)(b >> 32));          \
-        z += __longlong_as_double((long long)(((unsigned long long)hi << 32) | lo));                \
-    }
-    PB_STEP(8) PB_STEP(4) PB_STEP(2) PB_STEP(1)
-#undef PB_STEP
-    return z;
+    const unsigned long long b = (unsigned long long)__double_as_longlong(z);
+    const uint32_t lo = (uint32_t)b, hi = (uint32_t)(b >> 32);
+    // the swap leaves (own, partner's) in one half of the lanes and (partner's, own) in the other
+    const auto l = D == 16 ? __builtin_amdgcn_permlane16_swap(lo, lo, false, false)
+                           : __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto h = D == 16 ? __builtin_amdgcn_permlane16_swap(hi, hi, false, false)
+                           : __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    return __longlong_as_double((long long)(((unsigned long long)h[0] << 32) | l[0])) +
+           __longlong_as_double((long long)(((unsigned long long)h[1] << 32) | l[1]));
 }
 
 // Per-lane constants of the 16 x 16 transpose of 2-bit digits across a row of 16 lanes: lane L enters with the 32-bit
@@ -448,48 +442,58 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     // The row tile is complete in every slice: scale and store it.  (The barrier per row tile also
                     // keeps the waves of a workgroup on one contiguous region of the weight stream; letting them
                     // drift apart over several row tiles measured 5-15 % slower.)
-                    // A task = (vector, four rows); lane = (row of the four, bitlayer): every lane converts one
-                    // (row, bitlayer) sum, the 16 lanes of a row add up their scaled terms.  The waves share the
-                    // 4 * NV tasks out, so that none of them is late for the next barrier.
+                    // A lane per (vector, row), or with one or two vectors per workgroup 4 or 2 lanes that share out the
+                    // bitlayers: scaled sums in fp64, then the sum over those lanes (rows of 16 lanes 16 or 32 apart).
+                    // The waves take turns, so that none of them is always late for the next barrier.
                     pi = 0;
                     __syncthreads();
-                    const int rq = lane >> 4, il = lane & 15;
-                    for (int task = wave; task < 4 * NV; task += nwaves) {
-                        const int v = task >> 2, jrow = (task & 3) * 4 + rq, n = n0 + v;
+                    constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per output
+                    constexpr int RW = (NV * LG * kTileRows + 63) / 64; // waves that one row tile's outputs occupy
+                    for (int duty = (wave + nwaves - (pr * RW) % nwaves) % nwaves; duty < RW; duty += nwaves) {
+                        const int slot = duty * 4 + (lane >> 4);
+                        const int v = slot / LG, lg = slot % LG, jrow = lane & 15, n = n0 + v;
                         const int prow = (rt0 + pr) * kTileRows + jrow;
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
-                        const bool live = n < a.batch && row >= 0 && row < a.R;
-                        int s_lo = 0, s_hi = 0;
-                        if (il < m) {
-                            int *src = &abuf[pr & 1][v][il][0][jrow];
-                            s_lo = src[0];
-                            s_hi = src[kTileRows];
-                            src[0] = 0;
-                            src[kTileRows] = 0;
-                        }
-                        // A_i = lo + hi * 2^16 exactly: 0 <= lo < 2^30, |hi| < 2^30
-                        const long long Ai = (long long)s_lo + ((long long)s_hi << 16);
-                        if (a.A) {
-                            if (live && il < m) a.A[((size_t)il * a.batch + n) * (size_t)a.R + row] = Ai;
-                            continue;
-                        }
-                        const double z = row_sum16((double)s_scales[il] * (double)Ai);
-                        float y = (float)(z * a.out_scale);
-                        if (a.bias && live) y += a.bias[row];
-                        if (a.c_prev) {
-                            // LSTM cell: the four rows of the task are the gates i, f, g, o of one unit (row = unit
-                            // for gate i); lane 0 updates the unit
-                            const float gi = lane_value<0>(y), gf = lane_value<16>(y);
-                            const float gg = lane_value<32>(y), go = lane_value<48>(y);
-                            if (lane == 0 && live) {
-                                const size_t at = (size_t)n * a.gate_h + (size_t)row;
-                                const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
-                                a.c_out[at] = cn;
-                                a.h_out[at] = sigmoid_f(go) * tanhf(cn);
+                        const bool live = v < NV && n < a.batch && row >= 0 && row < a.R;
+                        int *src = &abuf[pr & 1][v < NV ? v : 0][lg][0][jrow];
+                        double z = 0.0;
+                        if (v < NV) {
+                            for (int i = lg; i < m; i += LG, src += LG * 2 * kTileRows) {
+                                const int s_lo = src[0], s_hi = src[kTileRows];
+                                src[0] = 0;
+                                src[kTileRows] = 0;
+                                if (a.A) {
+                                    // A_i = lo + hi * 2^16 exactly: 0 <= lo < 2^30, |hi| < 2^30
+                                    if (live)
+                                        a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
+                                            (long long)s_lo + ((long long)s_hi << 16);
+                                } else {
+                                    z = fma((double)s_scales[i], fma((double)s_hi, 65536.0, (double)s_lo), z);
+                                }
                             }
-                        } else {
-                            if (a.relu) y = fmaxf(y, 0.0f);
-                            if (live && il == 0) a.Y[(size_t)n * a.R + row] = y;
+                        }
+                        if (LG >= 2) z = add_across<16>(z);
+                        if (LG == 4) z = add_across<32>(z);
+                        if (!a.A) {
+                            float y = (float)(z * a.out_scale);
+                            if (a.bias && live) y += a.bias[row];
+                            if (a.c_prev) {
+                                // LSTM cell: the four lanes of a quad hold the gates i, f, g, o of one unit (row = unit
+                                // for gate i); the first lane of the quad updates the unit
+                                const float gi = __uint_as_float(dpp_mov<0x00>(__float_as_uint(y)));
+                                const float gf = __uint_as_float(dpp_mov<0x55>(__float_as_uint(y)));
+                                const float gg = __uint_as_float(dpp_mov<0xAA>(__float_as_uint(y)));
+                                const float go = __uint_as_float(dpp_mov<0xFF>(__float_as_uint(y)));
+                                if ((lane & 3) == 0 && live && lg == 0) {
+                                    const size_t at = (size_t)n * a.gate_h + (size_t)row;
+                                    const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
+                                    a.c_out[at] = cn;
+                                    a.h_out[at] = sigmoid_f(go) * tanhf(cn);
+                                }
+                            } else {
+                                if (a.relu) y = fmaxf(y, 0.0f);
+                                if (live && lg == 0) a.Y[(size_t)n * a.R + row] = y;
+                            }
                         }
                     }
                     ++pr;
