@@ -162,6 +162,20 @@ int pb_matmul_bias_act(const void *packed, const float *scales, const pb_desc *d
 int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
                   void *workspace, void *stream);
 
+/* The accumulators as the matrix-core kernel holds them when it multiplies two
+ * adjacent bitlayers in one instruction (Section 3.4: bitlayers stacked in one
+ * operation; the scales of Algorithm 1 halve from bitlayer to bitlayer, so
+ * s_(i) A_(i) + s_(i+1) A_(i+1) = s_(i+1) (2 A_(i) + A_(i+1))).  The units are
+ * bitlayer 0 alone, the pairs (1, 2), (3, 4), ..., and a last single bitlayer
+ * if bits_used is even; P[0] = A_0, P[p] = 2 A_(2p-1) + A_(2p) for a pair,
+ * P[last] = A_(bits_used-1) for the single one.
+ * A: [bits_used / 2 + 1][batch][rows] int64, written.  Tiled layouts only
+ * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1).  pb_matmul takes this route by itself
+ * when scales[i] == 2 * scales[i + 1] holds for every pair, else it multiplies
+ * bitlayer by bitlayer. */
+int pb_matmul_acc_pairs(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
+                        void *workspace, void *stream);
+
 /* The two halves of pb_matmul, for callers that apply several weight matrices
  * to the same activations (or that time the halves separately):
  * pb_act_prep converts X to fixed point and writes its bit planes and plane

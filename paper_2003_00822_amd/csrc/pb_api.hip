@@ -111,7 +111,7 @@ int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream)
 
 static int matmul_common(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X0,
                          int cols0, const float *X1, int cols1, int batch, float *Y, int64_t *A, void *workspace,
-                         void *stream, const pb::Epilogue &ep = pb::Epilogue())
+                         void *stream, const pb::Epilogue &ep = pb::Epilogue(), bool pairs_out = false)
 {
     pb::Layout L;
     int rc = check_desc(d, &L);
@@ -128,7 +128,8 @@ static int matmul_common(const void *packed, const float *scales, const pb_desc 
     if (pb::is_tile16(L.layout))   // conversion, bit transpose, product and epilogue in one launch
         return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                           d->act_bits, X0, cols0, X1, cols1, nullptr, batch, Y,
-                                          reinterpret_cast<long long *>(A), ep, st));
+                                          reinterpret_cast<long long *>(A), pairs_out, ep, st));
+    if (pairs_out) return PB_EINVAL;   // only the tiled layouts multiply bitlayer pairs
     char *ws = static_cast<char *>(workspace);
     int *meta = reinterpret_cast<int *>(ws + pb::ws_meta_off(L, batch));
     uint32_t *planes = reinterpret_cast<uint32_t *>(ws + pb::ws_planes_off(L, batch));
@@ -166,6 +167,14 @@ int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const flo
     return matmul_common(packed, nullptr, d, bits_used, X, d->cols, nullptr, 0, batch, nullptr, A, workspace, stream);
 }
 
+int pb_matmul_acc_pairs(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
+                        void *workspace, void *stream)
+{
+    if (!A || !d) return PB_EINVAL;
+    return matmul_common(packed, nullptr, d, bits_used, X, d->cols, nullptr, 0, batch, nullptr, A, workspace, stream,
+                         pb::Epilogue(), true);
+}
+
 int pb_act_prep(const pb_desc *d, const float *X, int batch, void *workspace, void *stream)
 {
     pb::Layout L;
@@ -198,7 +207,7 @@ int pb_matmul_prepared(const void *packed, const float *scales, const pb_desc *d
     const uint32_t *planes = reinterpret_cast<const uint32_t *>(ws + pb::ws_planes_off(L, batch));
     if (pb::is_tile16(L.layout))
         return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
-                                          d->act_bits, nullptr, 0, nullptr, 0, planes, batch, Y, nullptr,
+                                          d->act_bits, nullptr, 0, nullptr, 0, planes, batch, Y, nullptr, false,
                                           pb::Epilogue(), static_cast<hipStream_t>(stream)));
     return hip_status(pb::launch_matvec(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                         planes, meta, batch, Y, nullptr, static_cast<hipStream_t>(stream)));

@@ -36,7 +36,7 @@ struct Epilogue {
 };
 int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
-                int batch, float *Y, long long *A, const Epilogue &ep, hipStream_t st);
+                int batch, float *Y, long long *A, bool pairs_out, const Epilogue &ep, hipStream_t st);
 
 // logistic function of the LSTM gates (one definition for the fused and the stand-alone cell update)
 __device__ __forceinline__ float sigmoid_f(float v) { return 1.0f / (1.0f + expf(-v)); }

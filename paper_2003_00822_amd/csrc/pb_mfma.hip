@@ -21,6 +21,13 @@
 // flipped, all 16 digits unsigned), and A = sum w x' - 2^31 * popcount(w): the popcount
 // of the weight words of a block is four ALU operations per lane.
 //
+// Two bitlayers per instruction.  The scales of Algorithm 1 halve from one bitlayer to the next, so
+// s_(i) A_(i) + s_(i+1) A_(i+1) = s_(i+1) (2 A_(i) + A_(i+1)): the weight operand carries the base-4 digit
+// 2 w_(i) + w_(i+1) (FP4 code = digit again) and one instruction does the work of two.  The sign bitlayer stays
+// alone (its scale has the other sign), then come the pairs (1, 2), (3, 4), ... and a last single bitlayer if
+// bits_used is even.  The kernel checks scales[i] == 2 scales[i + 1] itself and multiplies bitlayer by bitlayer
+// when that does not hold (any other scales are legal input).
+//
 // Operands.  A (16 x 128) = 16 digit rows x 128 columns, B (128 x 16) = 128 columns x
 // 16 weight rows, D (16 x 16): lane l of D holds row j = l % 16 of the weights and
 // the digits 4 * (l / 16) + c in its four registers c, so the digit weighting is
@@ -55,6 +62,7 @@ struct MfmaArgs {
     const float *scales;
     float *Y;
     long long *A;
+    int pairs_out;              // A receives the sums of the bitlayer pairs (2 A_(2p-1) + A_(2p)) instead of every A_i
     const float *bias;          // [rows] or null: added to the fp32 result
     const float *c_prev;        // non-null: LSTM cell update instead of the store of Y (gate-interleaved rows)
     float *h_out, *c_out;
@@ -195,6 +203,14 @@ __device__ __forceinline__ v8i weight_operand(uint32_t w)
     return r;
 }
 
+// Two packed words (the same columns of two bitlayers) -> the B operand of their digits 2 hi + lo (FP4 code = digit)
+__device__ __forceinline__ v8i weight_digit_operand(uint32_t hi, uint32_t lo)
+{
+    u32x4 d;
+    digit_operand_from_planes(lo, hi, d);
+    return as_operand(d);
+}
+
 __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 {
     // cbsz = blgp = 4: both operands FP4 (E2M1); block scales 2^0 (E8M0 code 127)
@@ -203,10 +219,12 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 
 // NQ: chunks of 512 columns per wave; NV: activation vectors whose digit rows a wave keeps (each weight block is
 // expanded once and multiplied with all of them); MAXS: most waves (column slices) per workgroup, which bounds
-// the registers a wave may use; RU: units (row tile, bitlayer) whose blocks a wave has in flight.  The host picks
+// the registers a wave may use; RU: units (row tile, bitlayer pair) whose blocks a wave has in flight.  The host picks
 // RU <= the units a wave has, so that a short stream pays for no empty ring slots; 4 KB in flight per wave
 // measured best (more requests in flight than that slow the short streams down and do not speed up the long ones).
-template <int NQ, int NV, int MAXS, int RU>
+// PAIR: a unit is a pair of bitlayers (worth it when several vectors share the expanded weights; with one vector
+// the half-empty units of the single bitlayers cost more than the saved instructions).
+template <int NQ, int NV, int MAXS, int RU, bool PAIR>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 {
     // Units requested before the activations have arrived (a head start that keeps HBM busy during the transpose);
@@ -215,7 +233,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #define PB_MFMA_PRE 2
 #endif
     constexpr int PRE = NQ >= 4 ? (PB_MFMA_PRE < 1 ? PB_MFMA_PRE : 1) : (RU < PB_MFMA_PRE ? RU : PB_MFMA_PRE);
-    // sums per vector, bitlayer, half (digits 0-7 in units of 1, digits 8-15 in units of 2^16) and row; two buffers,
+    // sums per vector, bitlayer (or pair), half (digits 0-7 in units of 1, digits 8-15 in units of 2^16) and row; two buffers,
     // used by alternate row tiles
     __shared__ int abuf[2][NV][PB_MAX_BITS][2][kTileRows];
     __shared__ float s_scales[PB_MAX_BITS];
@@ -229,34 +247,51 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int nq = min(NQ, a.cq - q0);                          // chunks it really has (>= 1 by construction)
     const int rt0 = blockIdx.x * a.rounds_per_wg;
     const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
-    const int U = rounds * m;
+    // units of a row tile: bitlayer 0, the pairs (1, 2), (3, 4), ..., and a last single bitlayer if m is even
+    const int mp = PAIR ? m / 2 + 1 : m;
+    const int U = rounds * mp;
 
-    // layer scales, lane i holds scales[i]: the oldest load of the wave, so that no later wait is held up by it;
-    // parked in LDS once the digit rows are built (the barrier before the first final sum orders that store)
+    // layer scales, lane i holds scales[i] (and the next one, for the check of the pairs): the oldest loads of
+    // the wave, so that no later wait is held up by them; parked in LDS once the digit rows are built (the
+    // barrier before the first final sum orders that store)
     const float scv = (a.scales && lane < m) ? a.scales[lane] : 0.0f;
+    const float scn = (PAIR && a.scales && lane + 1 < m) ? a.scales[lane + 1] : 0.0f;
 
-    // ---- the weight stream of this wave: unit u = (round r, bitlayer i), NQ blocks of 1 KB each ----
+    // ---- the weight stream of this wave: unit u = (round r, pair p): NQ blocks of 1 KB of the pair's low bitlayer
+    // (2 p, or the single one) and NQ of its high bitlayer (2 p - 1, if the unit is a pair) ----
     const size_t base_off = (size_t)rt0 * a.round_step + (size_t)q0 * 1024;
     const char *base = reinterpret_cast<const char *>(a.packed) + base_off;
     const uint32_t avail = (uint32_t)(a.packed_bytes - base_off);
     const int voff = lane * 16;
-    u32x4 ring[RU][NQ];
-    uint32_t ld_soff = 0;
-    int ld_i = 0, ld_u = 0;
-    auto issue = [&](u32x4 (&dst)[NQ]) {
+    constexpr int SB = PAIR ? 2 * NQ : NQ;   // blocks of a unit
+    u32x4 ring[RU][SB];
+    uint32_t ld_round = 0;
+    int ld_p = 0, ld_u = 0;
+    auto issue = [&](u32x4 (&dst)[SB]) {
         // past the last unit, and for chunks beyond the end of a ragged last slice, the descriptor has 0 records:
         // every lane is out of range, the load returns 0 and moves no data (no branch, so the compiler counts
         // the loads in flight exactly)
+        const int lo_layer = !PAIR ? ld_p : (ld_p == 0 ? 0 : min(2 * ld_p, m - 1));
+        const bool has_hi = PAIR && ld_p >= 1 && 2 * ld_p <= m - 1;
+        const uint32_t lo_off = ld_round + (uint32_t)lo_layer * a.layer_step;
+        const uint32_t hi_off = has_hi ? lo_off - a.layer_step : lo_off;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<char *>(base), 0, (ld_u < U && q < nq) ? (int)avail : 0, 0x00020000);
-            dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)ld_soff, /*nt*/ 2);
+            dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)lo_off, /*nt*/ 2);
+        }
+        if constexpr (PAIR) {
+#pragma unroll
+            for (int q = 0; q < NQ; ++q) {
+                const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<char *>(base), 0, (ld_u < U && has_hi && q < nq) ? (int)avail : 0, 0x00020000);
+                dst[NQ + q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)hi_off, /*nt*/ 2);
+            }
         }
         __builtin_amdgcn_sched_barrier(0x7);
         ++ld_u;
-        if (++ld_i == m) { ld_i = 0; ld_soff += a.round_step - (uint32_t)(m - 1) * a.layer_step; }
-        else ld_soff += a.layer_step;
+        if (++ld_p == mp) { ld_p = 0; ld_round += a.round_step; }
     };
 
     // LDS sums start at zero.  The barrier that orders this is taken after every wave has REQUESTED its activations
@@ -395,58 +430,96 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         }
     }
     if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
+    // pairs are merged if every pair's scales are in the ratio 2 (then s_hi A_hi + s_lo A_lo = s_lo (2 A_hi + A_lo))
+    bool merged = PAIR && a.pairs_out != 0;
+    if (PAIR && !a.A) {
+        const bool off = (lane & 1) && lane + 1 < m && !(scv == 2.0f * scn);
+        merged = __builtin_amdgcn_ballot_w64(off) == 0;
+    }
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
     // per-lane digit weights: register c holds digit 4 kb + c, which weighs 4^(4 kb + c); lanes kb = 0, 1 sum
     // digits 0-7 (bits 0-15 of x') in units of 1, lanes kb = 2, 3 digits 8-15 in units of 2^16
+    // (the products are digit * 1 bitlayer by bitlayer and digit * digit / 4 with merged pairs)
     float kw[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * c + 8 * (kb & 1)));
+    for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * c + 8 * (kb & 1) + (merged ? 2 : 0)));
 
     const int j = lane & 15, half = lane >> 5;
-    int pi = 0, pr = 0;   // bitlayer and round of the unit being multiplied
+    int pp = 0, pr = 0;   // pair and round of the unit being multiplied
+    // the end of a pass: sd = sum of the weight digits of this lane's words (row j, k-block kb), `set` = its sums in LDS
+    auto finish = [&](const v4f (&acc)[NV], int sd, int set) {
+        // sum w x_q = sum w x' - 2^31 * sum w.  The lanes of the upper half (units of 2^16) subtract 2^15 times
+        // the digit sum of their own k-block and of the one 32 lanes below.
+        const auto sds = __builtin_amdgcn_permlane32_swap((uint32_t)sd, (uint32_t)sd, false, false);
+        const int corr = half ? (int)((sds[0] + sds[1]) << 15) : 0;
+        // digit weighting inside the lane.  Sums of digit products are <= 9 * 2048 (a slice has at most 2048
+        // columns), so c0 + 4 c1 + 16 c2 + 64 c3 < 2^21 and its multiple by 2^8 is exact in fp32 and < 2^29.
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            const float f = acc[v][0] * kw[0] + acc[v][1] * kw[1] + acc[v][2] * kw[2] + acc[v][3] * kw[3];
+            atomicAdd(&abuf[pr & 1][v][set][half][j], (int)f - corr);
+        }
+    };
     for (int u0 = 0; u0 < U; u0 += RU) {
 #pragma unroll
         for (int k = 0; k < RU; ++k) {
             if (u0 + k < U) {
-                v4f acc[NV];
+                const int lo_layer = !PAIR ? pp : (pp == 0 ? 0 : min(2 * pp, m - 1));
+                const bool has_hi = PAIR && pp >= 1 && 2 * pp <= m - 1;
+                // (chunks beyond a ragged last slice, and the absent high bitlayer of a single unit, are zero words)
+                if (PAIR && merged) {
+                    v4f acc[NV];
 #pragma unroll
-                for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
-                // (chunks beyond a ragged last slice multiply zero weights)
-                int pc = 0;   // set bits of this lane's weight words: row j, k-block kb
+                    for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                    int pcl = 0, pch = 0;
 #pragma unroll
-                for (int q = 0; q < NQ; ++q) {
-                    const u32x4 w = ring[k][q];
+                    for (int q = 0; q < NQ; ++q) {
+                        const u32x4 wl = ring[k][q], wh = ring[k][PAIR ? NQ + q : q];
 #pragma unroll
-                    for (int t = 0; t < 4; ++t) {
-                        const v8i b = weight_operand(w[t]);
-                        pc += __builtin_popcount(w[t]);
+                        for (int t = 0; t < 4; ++t) {
+                            const v8i b = weight_digit_operand(wh[t], wl[t]);
+                            pcl += __builtin_popcount(wl[t]);
+                            pch += __builtin_popcount(wh[t]);
 #pragma unroll
-                        for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
+                            for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
+                        }
+                    }
+                    finish(acc, 2 * pch + pcl, pp);
+                } else {
+#pragma unroll
+                    for (int h = PAIR ? 1 : 0; h >= 0; --h) {
+                        if (h == 1 && !has_hi) continue;
+                        v4f acc[NV];
+#pragma unroll
+                        for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                        int pc = 0;
+#pragma unroll
+                        for (int q = 0; q < NQ; ++q) {
+                            const u32x4 w = ring[k][h * NQ + q];
+#pragma unroll
+                            for (int t = 0; t < 4; ++t) {
+                                const v8i b = weight_operand(w[t]);
+                                pc += __builtin_popcount(w[t]);
+#pragma unroll
+                                for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
+                            }
+                        }
+                        finish(acc, pc, lo_layer - h);
                     }
                 }
-                // sum w x_q = sum w x' - 2^31 * popcount(w).  The lanes of the upper half (units of 2^16) subtract
-                // 2^15 times the popcount of their own k-block and of the one 32 lanes below.
-                const auto pcs = __builtin_amdgcn_permlane32_swap((uint32_t)pc, (uint32_t)pc, false, false);
-                const int corr = half ? (int)((pcs[0] + pcs[1]) << 15) : 0;
-                // digit weighting inside the lane.  Sums of digits are <= 3 * 2048 (a slice has at most 2048
-                // columns), so c0 + 4 c1 + 16 c2 + 64 c3 < 2^20 and its multiple by 2^8 is exact in fp32 and < 2^28.
-#pragma unroll
-                for (int v = 0; v < NV; ++v) {
-                    const float f = acc[v][0] * kw[0] + acc[v][1] * kw[1] + acc[v][2] * kw[2] + acc[v][3] * kw[3];
-                    atomicAdd(&abuf[pr & 1][v][pi][half][j], (int)f - corr);
-                }
-                if (++pi == m) {
+                if (++pp == mp) {
                     // The row tile is complete in every slice: scale and store it.  (The barrier per row tile also
                     // keeps the waves of a workgroup on one contiguous region of the weight stream; letting them
                     // drift apart over several row tiles measured 5-15 % slower.)
                     // A lane per (vector, row), or with one or two vectors per workgroup 4 or 2 lanes that share out the
                     // bitlayers: scaled sums in fp64, then the sum over those lanes (rows of 16 lanes 16 or 32 apart).
                     // The waves take turns, so that none of them is always late for the next barrier.
-                    pi = 0;
+                    pp = 0;
                     __syncthreads();
+                    const int nsets = merged ? mp : m;
                     constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per output
                     constexpr int RW = (NV * LG * kTileRows + 63) / 64; // waves that one row tile's outputs occupy
                     for (int duty = (wave + nwaves - (pr * RW) % nwaves) % nwaves; duty < RW; duty += nwaves) {
@@ -458,17 +531,20 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         int *src = &abuf[pr & 1][v < NV ? v : 0][lg][0][jrow];
                         double z = 0.0;
                         if (v < NV) {
-                            for (int i = lg; i < m; i += LG, src += LG * 2 * kTileRows) {
-                                const int s_lo = src[0], s_hi = src[kTileRows];
+                            for (int i = lg; i < nsets; i += LG, src += LG * 2 * kTileRows) {
+                                const uint32_t s_lo = (uint32_t)src[0];
+                                const int s_hi = src[kTileRows];
                                 src[0] = 0;
                                 src[kTileRows] = 0;
+                                // the sum is lo + hi * 2^16 exactly: 0 <= lo < 2^32 (unsigned), |hi| < 2^31
                                 if (a.A) {
-                                    // A_i = lo + hi * 2^16 exactly: 0 <= lo < 2^30, |hi| < 2^30
                                     if (live)
                                         a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
                                             (long long)s_lo + ((long long)s_hi << 16);
                                 } else {
-                                    z = fma((double)s_scales[i], fma((double)s_hi, 65536.0, (double)s_lo), z);
+                                    // a merged pair carries the scale of its low bitlayer
+                                    const int si = !merged ? i : (i == 0 ? 0 : min(2 * i, m - 1));
+                                    z = fma((double)s_scales[si], fma((double)s_hi, 65536.0, (double)s_lo), z);
                                 }
                             }
                         }
@@ -504,12 +580,15 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     }
 }
 
-// The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup, ring depth in units).
+// The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup, ring depth in units), each for
+// single bitlayers and for pairs.
 struct Variant {
     int nq, nv, maxs, ru;
-    const void *fn;
+    const void *fn, *fn_pair;
 };
-#define PB_VARIANT(NQ, NV, MAXS, RU) {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU>)}
+#define PB_VARIANT(NQ, NV, MAXS, RU)                                                      \
+    {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false>),   \
+     reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true>)}
 static const Variant kVariants[] = {
     PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
     PB_VARIANT(1, 2, 16, 1), PB_VARIANT(1, 2, 16, 2), PB_VARIANT(1, 2, 16, 4),
@@ -560,27 +639,30 @@ static int pick_ring(int vi, int units)
 
 // Workgroups of S waves that fit on the device at once (occupancy does not change while the process lives, so it
 // is looked up once per kernel variant and workgroup size).
-static int resident_workgroups(int variant, int S)
+static int resident_workgroups(int variant, int S, bool pair)
 {
-    static int cache[kNumVariants][kMaxSlices + 1];
-    int v = __atomic_load_n(&cache[variant][S], __ATOMIC_RELAXED);
+    static int cache[2][kNumVariants][kMaxSlices + 1];
+    int *slot = &cache[pair ? 1 : 0][variant][S];
+    int v = __atomic_load_n(slot, __ATOMIC_RELAXED);
     if (v > 0) return v;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kVariants[variant].fn, S * 64, 0) != hipSuccess)
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
+            &per_cu, pair ? kVariants[variant].fn_pair : kVariants[variant].fn, S * 64, 0) != hipSuccess)
         return 0;
     v = cus * per_cu;
-    if (v > 0) __atomic_store_n(&cache[variant][S], v, __ATOMIC_RELAXED);
+    if (v > 0) __atomic_store_n(slot, v, __ATOMIC_RELAXED);
     return v;
 }
 
 int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
-                int batch, float *Y, long long *A, const Epilogue &ep, hipStream_t st)
+                int batch, float *Y, long long *A, bool pairs_out, const Epilogue &ep, hipStream_t st)
 {
     MfmaArgs a;
     a.packed = packed; a.X0 = X0; a.X1 = X1; a.planes = planes; a.scales = scales; a.Y = Y; a.A = A;
+    a.pairs_out = (A && pairs_out) ? 1 : 0;
     a.bias = ep.bias; a.relu = ep.relu; a.c_prev = ep.c_prev; a.h_out = ep.h_out; a.c_out = ep.c_out;
     a.gate_h = L.gate_h;
     a.packed_bytes = packed_bytes(L);
@@ -601,7 +683,10 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     const int groups = (batch + var.nv - 1) / var.nv;
     // Workgroups: as many as are resident at once (so that every wave builds its planes once and the weight
     // stream never waits for a second round of workgroups to start), each with whole row tiles.
-    int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S);   // of the sibling that needs the most registers
+    // Bitlayer pairs when several vectors share the expanded weights (and for the parity hook of the pairs)
+    bool pair = a.pairs_out || (!A && batch >= 2);
+    if (const char *e = getenv("PB_TUNE_PAIR")) pair = a.pairs_out || (!A && atoi(e) != 0);
+    int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S, pair);   // of the sibling that needs the most registers
     if (capacity < 1) return (int)hipErrorInvalidValue;
     if (const char *e = getenv("PB_TUNE_WGS")) capacity = atoi(e);
     int wgs = capacity / groups;
@@ -610,8 +695,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
     void *args[] = {&a};
-    const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * bits_used)];
-    const hipError_t e = hipLaunchKernel(run.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
+    const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * (pair ? bits_used / 2 + 1 : bits_used))];
+    const hipError_t e = hipLaunchKernel(pair ? run.fn_pair : run.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
                                          0, st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
 }

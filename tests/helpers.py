@@ -30,3 +30,14 @@ def assert_y_close(y_gpu, y_ref, A_ref, scales, frac_bits=16, rtol=1e-5):
     bad = np.abs(y_gpu - y_ref) > tol
     assert not bad.any(), "fp32 mismatch at %s: gpu %s ref %s" % (
         np.argwhere(bad)[:5].tolist(), y_gpu[bad][:5], y_ref[bad][:5])
+
+
+def pair_sums(A, bits_used):
+    """What the matrix-core kernel accumulates when it multiplies two bitlayers at once, from the oracle's
+    per-bitlayer sums A [m, N, R]: bitlayer 0 alone, 2 A[2p-1] + A[2p] for the pairs, a last single bitlayer
+    if bits_used is even."""
+    m = bits_used
+    out = [A[0]]
+    for p in range(1, m // 2 + 1):
+        out.append(2 * A[2 * p - 1] + A[2 * p] if 2 * p <= m - 1 else A[m - 1])
+    return np.stack(out)

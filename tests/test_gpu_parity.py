@@ -7,7 +7,7 @@ torch = pytest.importorskip("torch")
 
 from oracle import pb_oracle as po
 from paper_2003_00822_amd import synth
-from tests.helpers import assert_y_close, oracle_reference
+from tests.helpers import assert_y_close, oracle_reference, pair_sums
 
 pytestmark = pytest.mark.gpu
 
@@ -52,6 +52,12 @@ def run_layer(pb, W, bits, X, m_list, frac_bits=16, act_bits=32, check_y=True, l
         bad = A_gpu != ref["A"]
         assert not bad.any(), "int64 accumulators differ at %s (R=%d C=%d bits=%d m=%d)" % (
             np.argwhere(bad)[:5].tolist(), R, C, bits, m)
+        if lin.desc.layout != LAYOUTS["popc"]:
+            # the sums of the bitlayer pairs, as the matrix-core kernel holds them on its usual route
+            P_gpu = lin.acc_pairs(Xd, m).cpu().numpy()
+            bad = P_gpu != pair_sums(ref["A"], m)
+            assert not bad.any(), "pair sums differ at %s (R=%d C=%d bits=%d m=%d)" % (
+                np.argwhere(bad)[:5].tolist(), R, C, bits, m)
         if check_y:
             Y_gpu = lin(Xd, m).cpu().numpy()
             assert_y_close(Y_gpu, ref["Y"], ref["A"], prep["scales"], frac_bits=frac_bits)
@@ -78,6 +84,28 @@ def test_every_bit_width_and_prefix(pb, layout, bits):
     W, X = synth.ragged(70, 200, batch=1, case=bits, xdist="uniform")
     print("bits", bits, flush=True)
     run_layer(pb, W, bits, X, list(range(1, bits + 1)), layout=layout)
+
+
+@pytest.mark.parametrize("bits", [2, 3, 5, 8])
+def test_scales_that_do_not_halve_are_applied_bitlayer_by_bitlayer(pb, bits):
+    """Any fp32 scales are legal input: the kernel merges bitlayer pairs only where scales[i] == 2 scales[i+1]."""
+    W, X = synth.ragged(50, 1500, batch=3, case=40 + bits, xdist="normal")
+    lin = pb.PackedLinear(dev(W), bits, max_batch=3)
+    ref = oracle_reference(W, bits, X, bits)
+    rng = np.random.default_rng(bits)
+    for kind in ("random", "one_off"):
+        sc = ref["scales"].copy()
+        if kind == "random":
+            sc = (sc * rng.uniform(0.5, 1.5, size=bits)).astype(np.float32)
+        else:
+            sc[-1] = np.nextafter(sc[-1], np.float32(1.0))   # a single ulp breaks the ratio of the last pair
+        lin.scales[:bits] = dev(sc)
+        Y = np.zeros((3, 50))
+        for i in range(bits):
+            Y += float(sc[i]) * ref["A"][i].astype(np.float64)
+        Y_ref = (Y * 2.0 ** -16).astype(np.float32)
+        print("bits", bits, kind, flush=True)
+        assert_y_close(lin(dev(X), bits).cpu().numpy(), Y_ref, ref["A"], sc)
 
 
 @pytest.mark.parametrize("xdist", ["normal", "uniform", "relu", "wide"])
