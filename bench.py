@@ -174,8 +174,8 @@ def main():
             "kernel_GBps": round(wbytes / t_kern / 1e9, 1),
             "kernel_hbm_frac": round(wbytes / t_kern / 1e9 / HBM_PEAK_GBS, 4),
         }
-        if mfma:   # 2 flops per (weight bit, plane): 32 planes
-            row["kernel_mfma_frac"] = round(2.0 * 32 * wbytes * 8 / t_kern / 1e12 / FP4_PEAK_TFLOPS, 4)
+        if mfma:   # flops of the matrix instructions issued: 2 per (weight bit, digit row), 16 digit rows = 32 planes
+            row["kernel_mfma_frac"] = round(2.0 * 16 * wbytes * 8 / t_kern / 1e12 / FP4_PEAK_TFLOPS, 4)
         else:      # one AND + one popcount-accumulate per (word, plane)
             row["kernel_alu_frac"] = round(2.0 * nplanes * (wbytes / 4) / t_kern / 1e9 / ALU_PEAK_GOPS, 4)
         per_m.append(row)
@@ -194,7 +194,7 @@ def main():
     roof_hbm = {"bound": "hbm", "achieved": round(avg_bytes / avg_kernel_s / 1e9, 1), "peak": HBM_PEAK_GBS,
                 "unit": "GB/s", "frac": round(hbm_frac, 4), "traffic": None}
     if mfma:
-        tflops = 2.0 * 32 * avg_bytes * 8 / avg_kernel_s / 1e12
+        tflops = 2.0 * 16 * avg_bytes * 8 / avg_kernel_s / 1e12   # issued: 16 digit rows (two planes each)
         cmp_frac = tflops / FP4_PEAK_TFLOPS
         roof_cmp = {"bound": "mfma", "achieved": round(tflops, 1), "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(cmp_frac, 4), "traffic": None}
@@ -231,14 +231,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "fp4 0/1 operands, fp32 exact counts, int64 accumulate" if mfma
+        "dtype": "fp4 base-4 digit operands, fp32 exact sums, int64 accumulate" if mfma
                  else "u32 popcount / int64 accumulate",
         "data": "synthetic",
         "config": {"workload": "FC %dx%d, weight bitlayers B=%d, bits_used swept 1..%d (one call each per step), "
                                "batch 1, x~N(0,1) as 32-bit fixed point" % (n, n, B, B),
                    "weights": "cold: %d copies (%d MiB) rotated" % (copies, copies * pbytes >> 20) if not args.warm
                    else "warm: one copy, cache resident",
-                   "kernel": "matrix cores (FP4 MFMA on 0/1 planes), one launch per call" if mfma
+                   "kernel": "matrix cores (FP4 MFMA, two bit planes per operand row), one launch per call" if mfma
                    else "AND + popcount, activation kernel + product kernel per call",
                    "launch": "eager" if args.eager else "hip graph replay (%d steps per graph)" % G,
                    "active_planes": nplanes},
@@ -509,7 +509,11 @@ def batch_sweep(torch, pb, synth, dev):
             row = {"kernel": name, "batch": N, "us_per_call": round(t * 1e6, 1),
                    "us_per_vector": round(t * 1e6 / N, 2), "Tbitmac_per_s": round(macs / t / 1e12, 1)}
             if name == "mfma":
-                row["mfma_frac"] = round(2 * macs / t / 1e12 / FP4_PEAK_TFLOPS, 4)
+                # matrix instructions issued: 16 digit rows (two planes each) per vector, and with more than one
+                # vector two bitlayers per instruction (units: bitlayer 0, pairs, a last single one)
+                units = m if N == 1 else m // 2 + 1
+                row["mfma_issued_TFLOPs"] = round(2.0 * 16 * n * n * units * N / t / 1e12, 1)
+                row["mfma_frac"] = round(2.0 * 16 * n * n * units * N / t / 1e12 / FP4_PEAK_TFLOPS, 4)
             rows.append(row)
         del lin
     return {"workload": "FC 8192x8192, B=8, bits_used=8, x~N(0,1), batch 1/4/16/64, weights warm", "rows": rows}

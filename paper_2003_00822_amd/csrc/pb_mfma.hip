@@ -87,7 +87,8 @@ __device__ __forceinline__ int32_t to_fixed_point(float x, float fscale, int32_t
     int32_t r;
     const float p = x * fscale;   // exact: a power of two
     asm("v_cvt_i32_f32 %0, %1" : "=v"(r) : "v"(p));
-    return min(max(r, imin), imax);
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(r), "v"(imin), "v"(imax));   // imin <= imax: the clamp
+    return r;
 }
 
 template <int CTRL>
@@ -127,17 +128,20 @@ __device__ __forceinline__ double add_across(double z)
 // bit J set (lower lane) / clear (upper lane); keep = the positions a lane keeps, rot = right-rotation that moves
 // the partner's digits into the others (>> 2 J for the upper lane, << 2 J for the lower).
 struct TransposeConsts {
-    uint32_t keep8, keep4, keep2, keep1;
-    uint32_t rot4, rot2, rot1;
+    uint32_t sel8, sel4;            // byte selectors of the stages that move whole bytes
+    uint32_t keep2, keep1;
+    uint32_t rot2, rot1;
+    uint32_t flip;                  // digit 15: its upper bit is bit 31 of the value
 };
 
 __device__ __forceinline__ TransposeConsts transpose_consts(int lane)
 {
     TransposeConsts c;
-    c.keep8 = (lane & 8) ? 0xFFFF0000u : 0x0000FFFFu;
-    c.keep4 = (lane & 4) ? 0xFF00FF00u : 0x00FF00FFu; c.rot4 = (lane & 4) ? 8 : 24;
+    c.sel8 = (lane & 8) ? 0x03020706u : 0x05040100u;   // (partner's, own) bytes 4-7, 0-3: halves exchanged
+    c.sel4 = (lane & 4) ? 0x03070105u : 0x06020400u;   // bytes exchanged
     c.keep2 = (lane & 2) ? 0xF0F0F0F0u : 0x0F0F0F0Fu; c.rot2 = (lane & 2) ? 4 : 28;
     c.keep1 = (lane & 1) ? 0xCCCCCCCCu : 0x33333333u; c.rot1 = (lane & 1) ? 2 : 30;
+    c.flip = (lane & 15) == 15 ? 0x22222222u : 0u;
     return c;
 }
 
@@ -151,8 +155,8 @@ __device__ __forceinline__ uint32_t transpose_stage(uint32_t x, uint32_t keep, u
 
 __device__ __forceinline__ uint32_t digit_transpose16(uint32_t x, const TransposeConsts &c)
 {
-    x = transpose_stage<8>(x, c.keep8, 16);
-    x = transpose_stage<4>(x, c.keep4, c.rot4);
+    x = __builtin_amdgcn_perm(row_xor<8>(x), x, c.sel8);
+    x = __builtin_amdgcn_perm(row_xor<4>(x), x, c.sel4);
     x = transpose_stage<2>(x, c.keep2, c.rot2);
     x = transpose_stage<1>(x, c.keep1, c.rot1);
     return x;
@@ -167,15 +171,16 @@ __device__ __forceinline__ int lane_column(int L)
 }
 
 // Transposed digits of the two half words (columns 0-15, 16-31) -> the four A-operand registers
-// (register r, nibble n = digit of column 4 n + r, FP4 code = the digit)
-__device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, u32x4 &dst)
+// (register r, nibble n = digit of column 4 n + r, FP4 code = the digit).  `flip` turns the digits of x_q into
+// those of x' = x_q + 2^31: the upper bit of digit 15.
+__device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, uint32_t flip, u32x4 &dst)
 {
     const uint32_t m0 = __builtin_amdgcn_perm(q, p, 0x05040100u);   // low halves of p and q
     const uint32_t m1 = __builtin_amdgcn_perm(q, p, 0x07060302u);   // high halves
-    dst.x = m0 & 0x33333333u;
-    dst.y = (m0 >> 2) & 0x33333333u;
-    dst.z = m1 & 0x33333333u;
-    dst.w = (m1 >> 2) & 0x33333333u;
+    dst.x = (m0 & 0x33333333u) ^ flip;
+    dst.y = ((m0 >> 2) & 0x33333333u) ^ flip;
+    dst.z = (m1 & 0x33333333u) ^ flip;
+    dst.w = ((m1 >> 2) & 0x33333333u) ^ flip;
 }
 
 // The same operand from the two plane words (bit c = column c) of a digit row
@@ -418,14 +423,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        // x' = x_q + 2^31 as an unsigned value: the top bit flipped
-                        const uint32_t X = 0x80000000u ^
+                        const uint32_t X =
                             (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][0]), a.fscale, a.imin, a.imax);
-                        const uint32_t Y = 0x80000000u ^
+                        const uint32_t Y =
                             (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][1]), a.fscale, a.imin, a.imax);
                         const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
                         // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
-                        digit_operand(digit_transpose16(sw[0], tc), digit_transpose16(sw[1], tc), pa[g + v][q][t]);
+                        digit_operand(digit_transpose16(sw[0], tc), digit_transpose16(sw[1], tc), tc.flip,
+                                      pa[g + v][q][t]);
                     }
         }
     }
