@@ -510,8 +510,8 @@ def batch_sweep(torch, pb, synth, dev):
                    "us_per_vector": round(t * 1e6 / N, 2), "Tbitmac_per_s": round(macs / t / 1e12, 1)}
             if name == "mfma":
                 # matrix instructions issued: 16 digit rows (two planes each) per vector, and with more than one
-                # vector two bitlayers per instruction (units: bitlayer 0, pairs, a last single one)
-                units = m if N == 1 else m // 2 + 1
+                # vector two bitlayers per instruction
+                units = m if N == 1 else (m + 1) // 2
                 row["mfma_issued_TFLOPs"] = round(2.0 * 16 * n * n * units * N / t / 1e12, 1)
                 row["mfma_frac"] = round(2.0 * 16 * n * n * units * N / t / 1e12 / FP4_PEAK_TFLOPS, 4)
             rows.append(row)

@@ -164,15 +164,17 @@ int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const flo
 
 /* The accumulators as the matrix-core kernel holds them when it multiplies two
  * adjacent bitlayers in one instruction (Section 3.4: bitlayers stacked in one
- * operation; the scales of Algorithm 1 halve from bitlayer to bitlayer, so
- * s_(i) A_(i) + s_(i+1) A_(i+1) = s_(i+1) (2 A_(i) + A_(i+1))).  The units are
- * bitlayer 0 alone, the pairs (1, 2), (3, 4), ..., and a last single bitlayer
- * if bits_used is even; P[0] = A_0, P[p] = 2 A_(2p-1) + A_(2p) for a pair,
- * P[last] = A_(bits_used-1) for the single one.
- * A: [bits_used / 2 + 1][batch][rows] int64, written.  Tiled layouts only
- * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1).  pb_matmul takes this route by itself
- * when scales[i] == 2 * scales[i + 1] holds for every pair, else it multiplies
- * bitlayer by bitlayer. */
+ * operation; the scales of Algorithm 1 halve from bitlayer to bitlayer and the
+ * sign bitlayer has scale -2 s_1, so s_(i) A_(i) + s_(i+1) A_(i+1) =
+ * s_(i+1) (+-2 A_(i) + A_(i+1))).  The units are the pairs (0, 1), (2, 3), ...
+ * and a last single bitlayer if bits_used is odd: P[0] = -2 A_0 + A_1 (A_0 if
+ * bits_used is 1), P[p] = 2 A_(2p) + A_(2p+1), P[last] = A_(bits_used-1) for a
+ * single one.
+ * A: [(bits_used + 1) / 2][batch][rows] int64, written.  Tiled layouts only
+ * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1).  pb_matmul with more than one vector
+ * takes this route by itself when scales[0] == -2 * scales[1] and scales[2p] ==
+ * 2 * scales[2p + 1] hold for every pair, else it multiplies bitlayer by
+ * bitlayer. */
 int pb_matmul_acc_pairs(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
                         void *workspace, void *stream);
 

@@ -23,10 +23,12 @@
 //
 // Two bitlayers per instruction.  The scales of Algorithm 1 halve from one bitlayer to the next, so
 // s_(i) A_(i) + s_(i+1) A_(i+1) = s_(i+1) (2 A_(i) + A_(i+1)): the weight operand carries the base-4 digit
-// 2 w_(i) + w_(i+1) (FP4 code = digit again) and one instruction does the work of two.  The sign bitlayer stays
-// alone (its scale has the other sign), then come the pairs (1, 2), (3, 4), ... and a last single bitlayer if
-// bits_used is even.  The kernel checks scales[i] == 2 scales[i + 1] itself and multiplies bitlayer by bitlayer
-// when that does not hold (any other scales are legal input).
+// 2 w_(i) + w_(i+1) (FP4 code = digit again) and one instruction does the work of two: the pairs are (0, 1),
+// (2, 3), ... and a last single bitlayer if bits_used is odd.  The sign bitlayer has the scale -2 s_1, so its
+// pair needs the digit w_1 - 2 w_0 = (2 (1 - w_0) + w_1) - 2: the bits of bitlayer 0 are complemented and
+// 2 * sum_c x_q[c] is subtracted, a sum that one more chain of instructions against an all-ones operand delivers
+// once per call.  The kernel checks scales[0] == -2 scales[1], scales[2p] == 2 scales[2p + 1] itself and
+// multiplies bitlayer by bitlayer when that does not hold (any other scales are legal input).
 //
 // Operands.  A (16 x 128) = 16 digit rows x 128 columns, B (128 x 16) = 128 columns x
 // 16 weight rows, D (16 x 16): lane l of D holds row j = l % 16 of the weights and
@@ -62,7 +64,7 @@ struct MfmaArgs {
     const float *scales;
     float *Y;
     long long *A;
-    int pairs_out;              // A receives the sums of the bitlayer pairs (2 A_(2p-1) + A_(2p)) instead of every A_i
+    int pairs_out;              // A receives the sums of the bitlayer pairs (-2 A_0 + A_1, 2 A_(2p) + A_(2p+1)) instead of every A_i
     const float *bias;          // [rows] or null: added to the fp32 result
     const float *c_prev;        // non-null: LSTM cell update instead of the store of Y (gate-interleaved rows)
     float *h_out, *c_out;
@@ -252,8 +254,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int nq = min(NQ, a.cq - q0);                          // chunks it really has (>= 1 by construction)
     const int rt0 = blockIdx.x * a.rounds_per_wg;
     const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
-    // units of a row tile: bitlayer 0, the pairs (1, 2), (3, 4), ..., and a last single bitlayer if m is even
-    const int mp = PAIR ? m / 2 + 1 : m;
+    // units of a row tile: the pairs (0, 1), (2, 3), ..., and a last single bitlayer if m is odd
+    const int mp = PAIR ? (m + 1) / 2 : m;
     const int U = rounds * mp;
 
     // layer scales, lane i holds scales[i] (and the next one, for the check of the pairs): the oldest loads of
@@ -263,7 +265,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const float scn = (PAIR && a.scales && lane + 1 < m) ? a.scales[lane + 1] : 0.0f;
 
     // ---- the weight stream of this wave: unit u = (round r, pair p): NQ blocks of 1 KB of the pair's low bitlayer
-    // (2 p, or the single one) and NQ of its high bitlayer (2 p - 1, if the unit is a pair) ----
+    // (2 p + 1, or the single one) and NQ of its high bitlayer (2 p, if the unit is a pair) ----
     const size_t base_off = (size_t)rt0 * a.round_step + (size_t)q0 * 1024;
     const char *base = reinterpret_cast<const char *>(a.packed) + base_off;
     const uint32_t avail = (uint32_t)(a.packed_bytes - base_off);
@@ -276,8 +278,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         // past the last unit, and for chunks beyond the end of a ragged last slice, the descriptor has 0 records:
         // every lane is out of range, the load returns 0 and moves no data (no branch, so the compiler counts
         // the loads in flight exactly)
-        const int lo_layer = !PAIR ? ld_p : (ld_p == 0 ? 0 : min(2 * ld_p, m - 1));
-        const bool has_hi = PAIR && ld_p >= 1 && 2 * ld_p <= m - 1;
+        const int lo_layer = !PAIR ? ld_p : min(2 * ld_p + 1, m - 1);
+        const bool has_hi = PAIR && 2 * ld_p + 1 <= m - 1;
         const uint32_t lo_off = ld_round + (uint32_t)lo_layer * a.layer_step;
         const uint32_t hi_off = has_hi ? lo_off - a.layer_step : lo_off;
 #pragma unroll
@@ -435,10 +437,11 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         }
     }
     if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
-    // pairs are merged if every pair's scales are in the ratio 2 (then s_hi A_hi + s_lo A_lo = s_lo (2 A_hi + A_lo))
+    // pairs are merged if every pair's scales are in the ratio 2, -2 for the sign bitlayer (then
+    // s_hi A_hi + s_lo A_lo = s_lo (+-2 A_hi + A_lo))
     bool merged = PAIR && a.pairs_out != 0;
     if (PAIR && !a.A) {
-        const bool off = (lane & 1) && lane + 1 < m && !(scv == 2.0f * scn);
+        const bool off = !(lane & 1) && lane + 1 < m && !(scv == (lane == 0 ? -2.0f : 2.0f) * scn);
         merged = __builtin_amdgcn_ballot_w64(off) == 0;
     }
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
@@ -453,9 +456,27 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * c + 8 * (kb & 1) + (merged ? 2 : 0)));
 
     const int j = lane & 15, half = lane >> 5;
+    // sum_c x_q[c] over the slice, as this lane's share of it in the form the sums below have (merged pairs only):
+    // the product with an operand of digits 1
+    int sx[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) sx[v] = 0;
+    if (PAIR && merged && m >= 2) {
+        const v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc);
+            const float f = acc[0] * kw[0] + acc[1] * kw[1] + acc[2] * kw[2] + acc[3] * kw[3];
+            sx[v] = (int)f - (half ? (256 * NQ) << 15 : 0);   // x_q = x' - 2^31 in each of the 512 NQ columns
+        }
+    }
     int pp = 0, pr = 0;   // pair and round of the unit being multiplied
     // the end of a pass: sd = sum of the weight digits of this lane's words (row j, k-block kb), `set` = its sums in LDS
-    auto finish = [&](const v4f (&acc)[NV], int sd, int set) {
+    auto finish = [&](const v4f (&acc)[NV], int sd, int set, bool sign_pair) {
         // sum w x_q = sum w x' - 2^31 * sum w.  The lanes of the upper half (units of 2^16) subtract 2^15 times
         // the digit sum of their own k-block and of the one 32 lanes below.
         const auto sds = __builtin_amdgcn_permlane32_swap((uint32_t)sd, (uint32_t)sd, false, false);
@@ -465,24 +486,27 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const float f = acc[v][0] * kw[0] + acc[v][1] * kw[1] + acc[v][2] * kw[2] + acc[v][3] * kw[3];
-            atomicAdd(&abuf[pr & 1][v][set][half][j], (int)f - corr);
+            // (the digits of the sign pair stand 2 too high in every column)
+            atomicAdd(&abuf[pr & 1][v][set][half][j], (int)f - corr - (sign_pair ? 2 * sx[v] : 0));
         }
     };
     for (int u0 = 0; u0 < U; u0 += RU) {
 #pragma unroll
         for (int k = 0; k < RU; ++k) {
             if (u0 + k < U) {
-                const int lo_layer = !PAIR ? pp : (pp == 0 ? 0 : min(2 * pp, m - 1));
-                const bool has_hi = PAIR && pp >= 1 && 2 * pp <= m - 1;
+                const int lo_layer = !PAIR ? pp : min(2 * pp + 1, m - 1);
+                const bool has_hi = PAIR && 2 * pp + 1 <= m - 1;
                 // (chunks beyond a ragged last slice, and the absent high bitlayer of a single unit, are zero words)
                 if (PAIR && merged) {
                     v4f acc[NV];
 #pragma unroll
                     for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
                     int pcl = 0, pch = 0;
+                    const bool sign_pair = pp == 0 && has_hi;
+                    const uint32_t inv = sign_pair ? 0xFFFFFFFFu : 0u;   // the sign bitlayer enters as 1 - w
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
-                        const u32x4 wl = ring[k][q], wh = ring[k][PAIR ? NQ + q : q];
+                        const u32x4 wl = ring[k][q], wh = ring[k][PAIR ? NQ + q : q] ^ inv;
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const v8i b = weight_digit_operand(wh[t], wl[t]);
@@ -492,7 +516,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                             for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
                         }
                     }
-                    finish(acc, 2 * pch + pcl, pp);
+                    finish(acc, 2 * pch + pcl, pp, sign_pair);
                 } else {
 #pragma unroll
                     for (int h = PAIR ? 1 : 0; h >= 0; --h) {
@@ -512,7 +536,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                                 for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
                             }
                         }
-                        finish(acc, pc, lo_layer - h);
+                        finish(acc, pc, lo_layer - h, false);
                     }
                 }
                 if (++pp == mp) {
@@ -537,18 +561,20 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         double z = 0.0;
                         if (v < NV) {
                             for (int i = lg; i < nsets; i += LG, src += LG * 2 * kTileRows) {
-                                const uint32_t s_lo = (uint32_t)src[0];
-                                const int s_hi = src[kTileRows];
+                                const int r_lo = src[0], s_hi = src[kTileRows];
                                 src[0] = 0;
                                 src[kTileRows] = 0;
-                                // the sum is lo + hi * 2^16 exactly: 0 <= lo < 2^32 (unsigned), |hi| < 2^31
+                                // the sum is lo + hi * 2^16 exactly: 0 <= lo < 2^32 (unsigned) and |hi| < 2^31, except
+                                // that the low half of the sign pair lies in [-2^31, 2^30] (signed)
+                                const long long s_lo =
+                                    (merged && i == 0 && m >= 2) ? (long long)r_lo : (long long)(uint32_t)r_lo;
                                 if (a.A) {
                                     if (live)
                                         a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
-                                            (long long)s_lo + ((long long)s_hi << 16);
+                                            s_lo + ((long long)s_hi << 16);
                                 } else {
                                     // a merged pair carries the scale of its low bitlayer
-                                    const int si = !merged ? i : (i == 0 ? 0 : min(2 * i, m - 1));
+                                    const int si = !merged ? i : min(2 * i + 1, m - 1);
                                     z = fma((double)s_scales[si], fma((double)s_hi, 65536.0, (double)s_lo), z);
                                 }
                             }
@@ -700,7 +726,7 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
     void *args[] = {&a};
-    const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * (pair ? bits_used / 2 + 1 : bits_used))];
+    const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used))];
     const hipError_t e = hipLaunchKernel(pair ? run.fn_pair : run.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
                                          0, st);
     return (int)(e != hipSuccess ? e : hipGetLastError());

@@ -276,7 +276,7 @@ class PackedLinear:
         X = X.reshape(-1, self.cols)
         batch = X.shape[0]
         m = bits_used or self.bits
-        A = torch.empty((m // 2 + 1, batch, self.rows), dtype=torch.int64, device=X.device)
+        A = torch.empty(((m + 1) // 2, batch, self.rows), dtype=torch.int64, device=X.device)
         pb_matmul_acc_pairs(self.packed, self.desc, m, X, batch, A, self.workspace)
         return A
 

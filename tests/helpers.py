@@ -34,10 +34,13 @@ def assert_y_close(y_gpu, y_ref, A_ref, scales, frac_bits=16, rtol=1e-5):
 
 def pair_sums(A, bits_used):
     """What the matrix-core kernel accumulates when it multiplies two bitlayers at once, from the oracle's
-    per-bitlayer sums A [m, N, R]: bitlayer 0 alone, 2 A[2p-1] + A[2p] for the pairs, a last single bitlayer
-    if bits_used is even."""
+    per-bitlayer sums A [m, N, R]: -2 A[0] + A[1] for the sign pair, 2 A[2p] + A[2p+1] for the others, a last
+    single bitlayer if bits_used is odd."""
     m = bits_used
-    out = [A[0]]
-    for p in range(1, m // 2 + 1):
-        out.append(2 * A[2 * p - 1] + A[2 * p] if 2 * p <= m - 1 else A[m - 1])
+    out = []
+    for p in range((m + 1) // 2):
+        if 2 * p + 1 <= m - 1:
+            out.append((-2 if p == 0 else 2) * A[2 * p] + A[2 * p + 1])
+        else:
+            out.append(A[m - 1])
     return np.stack(out)
