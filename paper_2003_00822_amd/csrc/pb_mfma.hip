@@ -185,11 +185,13 @@ __device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, uint32_t f
     dst.w = ((m1 >> 2) & 0x33333333u) ^ flip;
 }
 
-// The same operand from the two plane words (bit c = column c) of a digit row
+// The same operand from the two plane words (bit c = column c) of a digit row: p0 the lower plane, p1 the upper
 __device__ __forceinline__ void digit_operand_from_planes(uint32_t p0, uint32_t p1, u32x4 &dst)
 {
-    const uint32_t e = (p0 & 0x55555555u) | ((p1 & 0x55555555u) << 1);   // columns 4 n (bits 4 n) and 4 n + 2
-    const uint32_t o = ((p0 >> 1) & 0x55555555u) | (p1 & 0xAAAAAAAAu);   // columns 4 n + 1 and 4 n + 3
+    // digits of the even columns c at bits c, c + 1; of the odd columns c at bits c - 1, c
+    uint32_t e = (p0 & 0x55555555u) | ((p1 << 1) & ~0x55555555u);
+    uint32_t o = ((p0 >> 1) & 0x55555555u) | (p1 & ~0x55555555u);
+    asm("" : "+v"(e), "+v"(o));   // (keeps the two words whole: ten operations instead of fourteen)
     dst.x = e & 0x33333333u;
     dst.y = o & 0x33333333u;
     dst.z = (e >> 2) & 0x33333333u;
