@@ -258,6 +258,7 @@ def main():
         return
     out["same_gpu_references"] = same_gpu_references(torch, dev, W, X, per_m)
     if mfma:
+        out["same_gpu_references"]["fp4_matrix_calibration"] = mfma_calibration(torch, pb, dev)
         out["table1_analog"] = table1_analog(torch, pb, dev, W, X, out["same_gpu_references"]["fp32_matvec_us"])
     out["paper_reference"] = {
         "what": "Table 1 of the paper: kernel speedup over a Cutlass fp32 matrix-vector product at 4096 x 4096, "
@@ -346,6 +347,32 @@ def same_gpu_references(torch, dev, W, X, per_m):
             "fp32_matvec_us": round(t * 1e6, 2), "fp32_matvec_GBps": round(n * n * 4 / t / 1e9, 1),
             "speedup_vs_fp32": {str(r["bits_used"]): round(t * 1e6 / r["us_per_call"], 2) for r in per_m},
             "bound_32_over_bits_used": {str(r["bits_used"]): round(32.0 / r["bits_used"], 2) for r in per_m}}
+
+
+def mfma_calibration(torch, pb, dev):
+    """The rate of the product kernel's FP4 matrix instruction on this GPU (pb_calib_mfma: constant operands, two
+    waves per SIMD on every compute unit): alone, with the expansion of one packed weight word per four
+    instructions, and with the kernel's epilogue per chain of four.  On a SIMD the matrix and the vector-ALU
+    instructions take turns, so the third figure is the ceiling of the batched regime with this much ALU work."""
+    cus = torch.cuda.get_device_properties(dev).multi_processor_count
+    buf = torch.empty(cus, dtype=torch.float32, device=dev)
+    res = {}
+    for mode, name in ((0, "instructions_alone"), (1, "with_weight_expansion"), (2, "with_expansion_and_epilogue")):
+        ts = []
+        for iters in (200, 2200):
+            pb.pb_calib_mfma(mode, iters, cus, buf)
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            pb.pb_calib_mfma(mode, iters, cus, buf)
+            e1.record()
+            torch.cuda.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        flops = 65536.0 * 16 * 2000 * 8 * cus
+        tf = flops / (ts[1] - ts[0]) / 1e12
+        res[name] = {"TFLOPs": round(tf, 1), "frac_of_peak": round(tf / FP4_PEAK_TFLOPS, 4)}
+    return res
 
 
 def measured_traffic(kernel, n, B):

@@ -425,3 +425,14 @@ def test_errors_surface_as_status(pb):
     with pytest.raises(pb.PbError) as e:
         pb.pb_matmul(packed, sc, d, 4, X[:, 1:].contiguous()[:, :0].reshape(-1).new_zeros(65)[1:], 1, Y, ws)
     assert e.value.status == pb.PB_EALIGN
+
+
+def test_calibration_loop_runs_and_rejects_bad_arguments(pb):
+    out = torch.zeros(4, dtype=torch.float32, device="cuda")
+    for mode in (0, 1, 2):
+        pb.pb_calib_mfma(mode, 3, 4, out)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    for bad in ((3, 1, 1), (0, 0, 1), (0, 1, 0)):
+        with pytest.raises(Exception):
+            pb.pb_calib_mfma(bad[0], bad[1], bad[2], out)
