@@ -144,6 +144,22 @@ def test_bias_act_arguments_rejected_before_launch(pb):
     assert L.pb_matmul_bias_act(fake, fake, dp, 5, fake, 1, null, 0, fake, fake, null) == pb.PB_EINVAL   # bits_used
 
 
+def test_pair_hook_and_calibration_arguments_rejected_before_launch(pb):
+    L = pb.lib()
+    fake = ctypes.c_void_p(0x1000)
+    null = ctypes.c_void_p(0)
+    d = pb.pb_desc_init_layout(64, 64, 4, pb.PB_LAYOUT_ROWMAJOR_V1)
+    # the popcount layout has no bitlayer pairs
+    assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 4, fake, 1, fake, fake, null) == pb.PB_EINVAL
+    d = pb.pb_desc_init(64, 64, 4)
+    assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 4, fake, 1, null, fake, null) == pb.PB_EINVAL    # A null
+    assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 0, fake, 1, fake, fake, null) == pb.PB_EINVAL    # bits_used
+    assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 4, fake, 0, fake, fake, null) == pb.PB_EINVAL    # batch
+    for mode, iters, wgs, out in ((3, 1, 1, fake), (-1, 1, 1, fake), (0, 0, 1, fake), (0, 1, 0, fake),
+                                  (0, 1, 1, null), (0, (1 << 20) + 1, 1, fake), (0, 1, 65537, fake)):
+        assert L.pb_calib_mfma(mode, iters, wgs, out, null) == pb.PB_EINVAL
+
+
 def test_strerror(pb):
     assert pb.strerror(0) == "ok"
     for s in (pb.PB_EINVAL, pb.PB_EALIGN, pb.PB_ESIZE, pb.PB_EHIP):
