@@ -31,21 +31,29 @@ __device__ __forceinline__ float from_ordered_key(uint32_t k)
     return __uint_as_float((k & 0x80000000u) ? (k & 0x7FFFFFFFu) : ~k);
 }
 
-// max |W|, max W and min W in one pass (Section 3.3: the step of every quantizer comes from these)
+// max |W|, max W and min W in one pass (Section 3.3: the step of every quantizer comes from these).
+// 16-byte loads, one set of atomics per workgroup.
 __global__ __launch_bounds__(256) void k_stats(const float *__restrict__ W, size_t n, unsigned long long *scratch)
 {
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    __shared__ uint32_t part[3][4];
     uint32_t am = 0, hi = 0, lo = 0xFFFFFFFFu;
-    for (; i < n; i += stride) {
-        const float w = W[i];
+    auto take = [&](float w) {
         if (w == w) {
             const uint32_t a = __float_as_uint(fabsf(w)), k = ordered_key(w);
             am = a > am ? a : am;
             hi = k > hi ? k : hi;
             lo = k < lo ? k : lo;
         }
+    };
+    const size_t tid = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    const size_t n4 = n / 4;
+    const float4 *W4 = reinterpret_cast<const float4 *>(W);   // W is 16-byte aligned (checked on the host)
+    for (size_t i = tid; i < n4; i += stride) {
+        const float4 w = W4[i];
+        take(w.x); take(w.y); take(w.z); take(w.w);
     }
+    for (size_t i = n4 * 4 + tid; i < n; i += stride) take(W[i]);
     for (int off = 32; off > 0; off >>= 1) {
         const uint32_t a = (uint32_t)__shfl_xor((int)am, off, 64), h = (uint32_t)__shfl_xor((int)hi, off, 64);
         const uint32_t l = (uint32_t)__shfl_xor((int)lo, off, 64);
@@ -54,6 +62,15 @@ __global__ __launch_bounds__(256) void k_stats(const float *__restrict__ W, size
         lo = l < lo ? l : lo;
     }
     if ((threadIdx.x & 63) == 0) {
+        part[0][threadIdx.x >> 6] = am; part[1][threadIdx.x >> 6] = hi; part[2][threadIdx.x >> 6] = lo;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < 4; ++w) {
+            am = part[0][w] > am ? part[0][w] : am;
+            hi = part[1][w] > hi ? part[1][w] : hi;
+            lo = part[2][w] < lo ? part[2][w] : lo;
+        }
         atomicMax(&scratch[kSlotAbsMax], (unsigned long long)am);
         atomicMax(&scratch[kSlotMax], (unsigned long long)hi);
         atomicMin(&scratch[kSlotMin], (unsigned long long)lo);
@@ -232,7 +249,7 @@ int launch_quantize_pack(const float *W, const Layout &L, int quantizer, uint32_
     int blocks = (int)((n + 256 * 16 - 1) / (256 * 16));
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(k_stats, dim3(blocks), dim3(256), 0, st, W, n, scratch);
+    hipLaunchKernelGGL(k_stats, dim3(blocks < 1024 ? blocks : 1024), dim3(256), 0, st, W, n, scratch);
     if (quantizer == PB_QUANT_SIGN) hipLaunchKernelGGL(k_abs_sum, dim3(blocks), dim3(256), 0, st, W, n, scratch);
     if (quantizer == PB_QUANT_CLIP_SEARCH)
         hipLaunchKernelGGL(k_clip_err, dim3(blocks), dim3(256), 0, st, W, n, L.bits, scratch);
