@@ -50,6 +50,10 @@ def parse():
     ap.add_argument("--sweep-only", action="store_true",
                     help="only the bits_used sweep of the headline workload (the run the profiler summaries are made "
                          "from: every launch of the product kernel then belongs to the sweep)")
+    ap.add_argument("--batch-point", type=int, default=0, metavar="N",
+                    help="only the batched workload at one point: --size x --size (use 8192), bits_used = --bits, N "
+                         "vectors, --steps calls (the run the batched profiler summaries are made from; prints its own "
+                         "small JSON line, not the headline one)")
     ap.add_argument("--calib", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
@@ -73,6 +77,10 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     n, B = args.size, args.bits
+    if args.batch_point:
+        print(json.dumps(batch_point(torch, pb, synth, dev, n, B, args.batch_point, args.steps, args.layout)),
+              flush=True)
+        return
     std = {4096: 0.02, 8192: 0.01}.get(n, 0.01)
     W, X = synth.fc_square(n, std, batch=1, cfg=2 if n == 4096 else 5)
     Wd = torch.from_numpy(W).to(dev)
@@ -544,6 +552,33 @@ def batch_sweep(torch, pb, synth, dev):
             rows.append(row)
         del lin
     return {"workload": "FC 8192x8192, B=8, bits_used=8, x~N(0,1), batch 1/4/16/64, weights warm", "rows": rows}
+
+
+def batch_point(torch, pb, synth, dev, n, B, N, steps, layout):
+    """One point of the batched regime by itself (cfg 5 recipe: W ~N(0, 0.01), x ~N(0, 1)), eager launches."""
+    W, _ = synth.fc_square(n, 0.01, batch=1, cfg=5)
+    lay = pb.PB_LAYOUT_TILE16_V1 if layout == "mfma" else pb.PB_LAYOUT_ROWMAJOR_V1
+    lin = pb.PackedLinear(torch.from_numpy(W).to(dev), B, max_batch=N, layout=lay)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(200300822 + 5000)
+    X = torch.randn((N, n), device=dev, generator=gen)
+    Y = torch.empty((N, n), dtype=torch.float32, device=dev)
+    for _ in range(3):
+        pb.pb_matmul(lin.packed, lin.scales, lin.desc, B, X, N, Y, lin.workspace)
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        pb.pb_matmul(lin.packed, lin.scales, lin.desc, B, X, N, Y, lin.workspace)
+    e1.record()
+    torch.cuda.synchronize()
+    t = e0.elapsed_time(e1) * 1e-3 / steps
+    units = B if N == 1 else (B + 1) // 2
+    return {"workload": "FC %dx%d, B=bits_used=%d, batch %d, x~N(0,1), weights warm, kernel %s" % (n, n, B, N, layout),
+            "steps": steps, "us_per_call": round(t * 1e6, 1),
+            "Tbitmac_per_s": round(float(n) * n * B * 32 * N / t / 1e12, 1),
+            "mfma_issued_TFLOPs": round(2.0 * 16 * n * n * units * N / t / 1e12, 1) if layout == "mfma" else None}
 
 
 def cpu_baseline(W, X, B, layer_bytes):
