@@ -123,6 +123,15 @@ def test_batches_that_do_not_fill_a_vector_group(pb, layout, shape_batch):
     run_layer(pb, W, 3, X, [1, 3], layout=layout)
 
 
+def test_maximum_batch(pb, layout):
+    """PB_MAX_BATCH vectors in one call (many vector groups per row tile; the last group is full)."""
+    W, X = synth.ragged(20, 600, batch=pb.PB_MAX_BATCH, case=12, xdist="normal")
+    print("batch", pb.PB_MAX_BATCH, flush=True)
+    run_layer(pb, W, 3, X, [3], layout=layout)
+    # one vector short of a full last group
+    run_layer(pb, W, 4, X[: pb.PB_MAX_BATCH - 1], [2], layout=layout)
+
+
 def test_fixed_point_conversion(pb):
     u = 2.0 ** -16
     special = [0.0, 1.0, -2.0, 0.5 * u, -0.5 * u, 1.5 * u, -1.5 * u, 1.0 - 2.0 ** -24, 32767.998046875, 32768.0,
