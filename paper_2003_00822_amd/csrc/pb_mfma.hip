@@ -635,14 +635,28 @@ static const Variant kVariants[] = {
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
+// Tuning overrides from the environment (for sweeps over the variants), read once: 0 / -1 = not set.
+struct Tuning {
+    int nq, nv, ru, wgs, pair;
+    Tuning()
+    {
+        auto get = [](const char *name, int unset) { const char *e = getenv(name); return e ? atoi(e) : unset; };
+        nq = get("PB_TUNE_NQ", 0); nv = get("PB_TUNE_NV", 0); ru = get("PB_TUNE_RU", 0);
+        wgs = get("PB_TUNE_WGS", 0); pair = get("PB_TUNE_PAIR", -1);
+    }
+};
+static const Tuning &tuning()
+{
+    static const Tuning t;
+    return t;
+}
+
 // As many vectors per wave as the batch has and the registers allow (each weight block is then read and expanded
 // once for all of them), then the smallest slice (most waves per row, shortest transpose per wave) whose slice
 // count fits a workgroup; ring depth 1 (the deeper rings are picked once the units per wave are known).
 static int pick_variant(const Layout &L, int batch)
 {
-    int want_nq = 0, want_nv = 0;
-    if (const char *e = getenv("PB_TUNE_NQ")) want_nq = atoi(e);
-    if (const char *e = getenv("PB_TUNE_NV")) want_nv = atoi(e);
+    const int want_nq = tuning().nq, want_nv = tuning().nv;
     int best = -1;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
@@ -659,8 +673,7 @@ static int pick_variant(const Layout &L, int batch)
 // The sibling of variant `vi` with the deepest ring that a wave with `units` units fills.
 static int pick_ring(int vi, int units)
 {
-    int want = 0;
-    if (const char *e = getenv("PB_TUNE_RU")) want = atoi(e);
+    const int want = tuning().ru;
     int best = vi;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
@@ -718,10 +731,10 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     // stream never waits for a second round of workgroups to start), each with whole row tiles.
     // Bitlayer pairs when several vectors share the expanded weights (and for the parity hook of the pairs)
     bool pair = a.pairs_out || (!A && batch >= 2);
-    if (const char *e = getenv("PB_TUNE_PAIR")) pair = a.pairs_out || (!A && atoi(e) != 0);
+    if (tuning().pair >= 0) pair = a.pairs_out || (!A && tuning().pair != 0);
     int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S, pair);   // of the sibling that needs the most registers
     if (capacity < 1) return (int)hipErrorInvalidValue;
-    if (const char *e = getenv("PB_TUNE_WGS")) capacity = atoi(e);
+    if (tuning().wgs > 0) capacity = tuning().wgs;
     int wgs = capacity / groups;
     if (wgs < 1) wgs = 1;
     if (wgs > L.rt_count) wgs = L.rt_count;
