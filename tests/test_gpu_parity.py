@@ -359,7 +359,8 @@ def test_bias_and_relu_epilogue(pb, lay, act):
 
 def test_lstm_fused_cell_small_ragged(pb):
     """Fused product + cell update (one launch) on shapes whose H is not a multiple of 4 and with a batch."""
-    for (H, I, N) in [(5, 7, 1), (38, 50, 3), (130, 70, 2), (37, 33, 1), (21, 1001, 2), (300, 2, 1)]:
+    for (H, I, N) in [(5, 7, 1), (38, 50, 3), (130, 70, 2), (37, 33, 1), (21, 1001, 2), (300, 2, 1), (38, 50, 6),
+                      (21, 1001, 11), (9, 515, 8)]:
         W, X = synth.ragged(4 * H, I + H, batch=N, case=19, xdist="uniform")
         rng = np.random.default_rng(19)
         bias = rng.normal(size=4 * H).astype(np.float32) * 0.1
