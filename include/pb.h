@@ -135,8 +135,10 @@ int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);
  *   x_q = trunc(x * 2^f) as a k-bit two's-complement integer (saturating;
  *   NaN -> 0), split into k bit planes with weights 2^j and -2^(k-1);
  *   A_i[r] = sum_j c_j * popcount(row r of bitlayer i AND plane j)  (exact, int64; computed as
- *            AND + popcount or as an exact 0/1 matrix product, depending on the layout)
- *   Y[r]   = fp32( sum_{i < bits_used} scales[i] * A_i[r] * 2^-f )  (sum in fp64)
+ *            AND + popcount or as an exact matrix product of the same bits, depending on the layout)
+ *   Y[r]   = fp32( sum_{i < bits_used} scales[i] * A_i[r] * 2^-f )  (sum in fp64; where two adjacent
+ *            scales are in the ratio of Algorithm 1 the tiled layouts may add the pair's integers first,
+ *            see pb_matmul_acc_pairs: the same sum up to the fp64 rounding of its terms)
  * Only the first `bits_used` bitlayers (sign layer and the next bits_used-1)
  * are read: the accuracy / speed knob of the abstract.
  *   packed, scales  as written by pb_quantize_pack (scales may be any fp32 values)
