@@ -627,7 +627,7 @@ static const Variant kVariants[] = {
     PB_VARIANT(1, 2, 16, 1), PB_VARIANT(1, 2, 16, 2), PB_VARIANT(1, 2, 16, 4),
     PB_VARIANT(1, 4, 8, 1),  PB_VARIANT(1, 4, 8, 2),  PB_VARIANT(1, 4, 8, 4),
     PB_VARIANT(1, 8, 8, 1),  PB_VARIANT(1, 8, 8, 2),  PB_VARIANT(1, 8, 8, 4),
-    PB_VARIANT(2, 1, 16, 1), PB_VARIANT(2, 1, 16, 2),
+    PB_VARIANT(2, 1, 16, 1), PB_VARIANT(2, 1, 16, 2), PB_VARIANT(2, 1, 16, 3),
     PB_VARIANT(2, 2, 8, 1),  PB_VARIANT(2, 2, 8, 2),
     PB_VARIANT(2, 4, 8, 1),  PB_VARIANT(2, 4, 8, 2),
     PB_VARIANT(4, 1, 8, 1),  PB_VARIANT(4, 1, 8, 2),
