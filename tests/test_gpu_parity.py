@@ -132,6 +132,24 @@ def test_maximum_batch(pb, layout):
     run_layer(pb, W, 4, X[: pb.PB_MAX_BATCH - 1], [2], layout=layout)
 
 
+def test_random_configurations(pb):
+    """Seeded random shapes, widths, prefixes, batches, activation formats and distributions on the matrix-core
+    layout: codes, per-bitlayer sums, pair sums and outputs against the oracle."""
+    rng = np.random.default_rng(200300822)
+    for case in range(120):
+        R = int(rng.integers(1, 160))
+        C = int(rng.choice([rng.integers(1, 700), rng.integers(700, 4200), rng.integers(4200, 9000)]))
+        N = int(rng.choice([1, 1, 2, 3, 5, 8, 9, 17]))
+        bits = int(rng.integers(1, 17))
+        m = sorted({int(rng.integers(1, bits + 1)), bits})
+        act_bits, frac_bits = [(32, 16), (32, 16), (16, 12), (8, 4), (24, 20)][int(rng.integers(0, 5))]
+        xdist = ["normal", "uniform", "relu", "wide"][int(rng.integers(0, 4))]
+        W, X = synth.ragged(R, C, batch=N, case=100 + case, xdist=xdist)
+        print("case", case, (R, C, N), "bits", bits, "m", m, "act", act_bits, frac_bits, xdist, flush=True)
+        lay = GATES if (R % 4 == 0 and case % 3 == 0) else LAYOUTS["mfma"]
+        run_layer(pb, W, bits, X, m, frac_bits=frac_bits, act_bits=act_bits, layout=lay)
+
+
 def test_fixed_point_conversion(pb):
     u = 2.0 ** -16
     special = [0.0, 1.0, -2.0, 0.5 * u, -0.5 * u, 1.5 * u, -1.5 * u, 1.0 - 2.0 ** -24, 32767.998046875, 32768.0,
