@@ -464,3 +464,50 @@ def test_calibration_loop_runs_and_rejects_bad_arguments(pb):
     for bad in ((3, 1, 1), (0, 0, 1), (0, 1, 0)):
         with pytest.raises(Exception):
             pb.pb_calib_mfma(bad[0], bad[1], bad[2], out)
+
+
+def test_graph_replay_matches_eager(pb):
+    """A captured sequence of calls (two FC layers with bias + ReLU, then an LSTM step) replayed several times with
+    new inputs and eager work in between gives the eager results bit for bit."""
+    rng = np.random.default_rng(77)
+    W1, X = synth.ragged(96, 300, batch=3, case=51, xdist="normal")
+    W2, _ = synth.ragged(64, 96, batch=3, case=52)
+    H = 16
+    Wl, _ = synth.ragged(4 * H, 64 + H, batch=3, case=53)
+    l1 = pb.PackedLinear(dev(W1), 6, max_batch=3)
+    l2 = pb.PackedLinear(dev(W2), 4, max_batch=3)
+    ll = pb.PackedLinear(dev(Wl), 5, max_batch=3, layout=GATES)
+    b1 = dev(rng.normal(size=96).astype(np.float32))
+    b2 = dev(rng.normal(size=64).astype(np.float32))
+    bl = dev(rng.normal(size=4 * H).astype(np.float32))
+    x = dev(X)
+    y1 = torch.empty((3, 96), device="cuda")
+    y2 = torch.empty((3, 64), device="cuda")
+    h = torch.zeros((3, H), device="cuda")
+    c = torch.zeros((3, H), device="cuda")
+    h_out = torch.empty_like(h)
+    c_out = torch.empty_like(c)
+
+    def forward():
+        pb.pb_matmul_bias_act(l1.packed, l1.scales, l1.desc, 5, x, 3, b1, pb.PB_ACT_RELU, y1, l1.workspace)
+        pb.pb_matmul_bias_act(l2.packed, l2.scales, l2.desc, 4, y1, 3, b2, pb.PB_ACT_NONE, y2, l2.workspace)
+        pb.pb_lstm_cell(ll.packed, ll.scales, ll.desc, 5, y2, 64, h, c, bl, h_out, c_out, 3, ll.workspace)
+
+    forward()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        forward()
+    for it in range(4):
+        x.copy_(dev(rng.normal(size=X.shape).astype(np.float32)))
+        h.copy_(dev(rng.normal(size=(3, H)).astype(np.float32)))
+        c.copy_(dev(rng.normal(size=(3, H)).astype(np.float32)))
+        g.replay()
+        torch.cuda.synchronize()
+        got = (y2.clone(), h_out.clone(), c_out.clone())
+        junk = torch.randn(1 << 16, device="cuda").sum()   # eager work between the replays
+        forward()
+        torch.cuda.synchronize()
+        assert torch.isfinite(junk)
+        for a_, b_ in zip(got, (y2, h_out, c_out)):
+            assert torch.equal(a_, b_), "replay %d differs from the eager run" % it
