@@ -609,8 +609,16 @@ def cpu_baseline(W, X, B, layer_bytes):
         for _ in range(reps):
             sweep(pool)
         dt = (time.perf_counter() - t0) / reps
+    # the same sweep on one thread (best of three)
+    dt1 = float("inf")
+    for _ in range(3):
+        t0 = time.perf_counter()
+        for m in range(1, B + 1):
+            po.matmul_words(lw, prep["scales"], m, C, X, want_A=False)
+        dt1 = min(dt1, time.perf_counter() - t0)
     step_bytes = layer_bytes * B * (B + 1) // 2
     return {"value": round(step_bytes / dt / 1e9, 3), "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "value_one_thread": round(step_bytes / dt1 / 1e9, 3),
             "sample": "oracle packed-word tier (uint64 AND+popcount, gcc -O2), full %dx%d layer, bits_used 1..%d, "
                       "%d sweeps, %.2f s each" % (R, C, B, reps, dt),
             "matvecs_per_s": round(B / dt, 2)}
