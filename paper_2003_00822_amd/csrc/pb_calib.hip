@@ -13,9 +13,9 @@ namespace pb {
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 
-// MODE 0: four independent instructions per step.  MODE 1: + the seven-operation expansion of a weight word and
-// its popcount per step.  MODE 2: + per chain of four steps and per accumulator four FMAs, a conversion and an
-// LDS atomic (the kernel's epilogue).
+// MODE 0: four independent instructions per step.  MODE 1: + the seven-operation expansion of a weight word per
+// step.  MODE 2: + per chain of four steps and per accumulator four FMAs, a conversion and an LDS atomic (the
+// kernel's epilogue).
 template <int MODE>
 __global__ __launch_bounds__(512) void k_calib_mfma(int iters, float *out)
 {
@@ -32,16 +32,13 @@ __global__ __launch_bounds__(512) void k_calib_mfma(int iters, float *out)
 #pragma unroll
     for (int v = 0; v < NV; ++v) c[v] = v4f{0.f, 0.f, 0.f, 0.f};
     uint32_t w = 0x9E3779B9u * (uint32_t)(lane + 1);
-    int total = 0;
     for (int i = 0; i < iters; ++i) {
-        int pc = 0;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             if (MODE >= 1) {
                 asm volatile("" : "+v"(w));   // a fresh word as far as the compiler knows
                 b[0] = (int)((w << 2) & 0x44444444u); b[1] = (int)((w << 1) & 0x44444444u);
                 b[2] = (int)(w & 0x44444444u);        b[3] = (int)((w >> 1) & 0x44444444u);
-                pc += __builtin_popcount(w);
             }
 #pragma unroll
             for (int v = 0; v < NV; ++v)
@@ -51,13 +48,12 @@ __global__ __launch_bounds__(512) void k_calib_mfma(int iters, float *out)
 #pragma unroll
             for (int v = 0; v < NV; ++v) {
                 const float f = c[v][0] + c[v][1] * 4.0f + c[v][2] * 16.0f + c[v][3] * 64.0f;
-                atomicAdd(&sums[lane], (int)f - pc);
+                atomicAdd(&sums[lane], (int)f);
                 c[v] = v4f{0.f, 0.f, 0.f, 0.f};
             }
         }
-        total += pc;
     }
-    float s = (float)total;
+    float s = (float)w;
 #pragma unroll
     for (int v = 0; v < NV; ++v) s += c[v][0] + c[v][1] + c[v][2] + c[v][3];
     __syncthreads();

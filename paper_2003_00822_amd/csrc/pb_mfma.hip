@@ -17,17 +17,17 @@
 // vector are the 16 rows of one A operand and the plane weights become 4^i.  The weight
 // bit is the code 2.0, so every product is the digit itself (0 .. 3), the fp32
 // accumulators hold integers below 2^24 and every sum is exact.
-// The sign plane: the digits are those of the offset value x' = x_q + 2^31 (top bit
-// flipped, all 16 digits unsigned), and A = sum w x' - 2^31 * popcount(w): the popcount
-// of the weight words of a block is four ALU operations per lane.
+// The sign plane: digit 15 (bits 31, 30) is the signed one, -2 b_31 + b_30, and E2M1 has
+// the values 0, 0.5, -1.0, -0.5 too (codes 0000, 0001, 1010, 1001): the two's-complement
+// value is sum_i 4^i digit_i with that one digit signed, nothing to correct afterwards.
 //
 // Two bitlayers per instruction.  The scales of Algorithm 1 halve from one bitlayer to the next, so
 // s_(i) A_(i) + s_(i+1) A_(i+1) = s_(i+1) (2 A_(i) + A_(i+1)): the weight operand carries the base-4 digit
 // 2 w_(i) + w_(i+1) (FP4 code = digit again) and one instruction does the work of two: the pairs are (0, 1),
 // (2, 3), ... and a last single bitlayer if bits_used is odd.  The sign bitlayer has the scale -2 s_1, so its
 // pair needs the digit w_1 - 2 w_0 = (2 (1 - w_0) + w_1) - 2: the bits of bitlayer 0 are complemented and
-// 2 * sum_c x_q[c] is subtracted, a sum that one more chain of instructions against an all-ones operand delivers
-// once per call.  The kernel checks scales[0] == -2 scales[1], scales[2p] == 2 scales[2p + 1] itself and
+// 2 * sum_c x_q[c] is subtracted, a sum that one more chain of instructions against an operand of digits 1
+// delivers once per call.  The kernel checks scales[0] == -2 scales[1], scales[2p] == 2 scales[2p + 1] itself and
 // multiplies bitlayer by bitlayer when that does not hold (any other scales are legal input).
 //
 // Operands.  A (16 x 128) = 16 digit rows x 128 columns, B (128 x 16) = 128 columns x
@@ -133,7 +133,10 @@ struct TransposeConsts {
     uint32_t sel8, sel4;            // byte selectors of the stages that move whole bytes
     uint32_t keep2, keep1;
     uint32_t rot2, rot1;
-    uint32_t flip;                  // digit 15: its upper bit is bit 31 of the value
+    // digit 15 is the signed one (bits 31, 30 of the value: -2 b31 + b30): the positions of its bits in a word of
+    // the transpose, non-zero in the lanes of digit 15 only
+    uint32_t top_hi;                // 0xAAAAAAAA: the upper bit of every digit
+    uint32_t top_hi_even, top_hi_odd;   // 0x22222222, 0x88888888: the same, digits at even / odd positions
 };
 
 __device__ __forceinline__ TransposeConsts transpose_consts(int lane)
@@ -143,7 +146,10 @@ __device__ __forceinline__ TransposeConsts transpose_consts(int lane)
     c.sel4 = (lane & 4) ? 0x03070105u : 0x06020400u;   // bytes exchanged
     c.keep2 = (lane & 2) ? 0xF0F0F0F0u : 0x0F0F0F0Fu; c.rot2 = (lane & 2) ? 4 : 28;
     c.keep1 = (lane & 1) ? 0xCCCCCCCCu : 0x33333333u; c.rot1 = (lane & 1) ? 2 : 30;
-    c.flip = (lane & 15) == 15 ? 0x22222222u : 0u;
+    const bool top = (lane & 15) == 15;
+    c.top_hi = top ? 0xAAAAAAAAu : 0u;
+    c.top_hi_even = top ? 0x22222222u : 0u;
+    c.top_hi_odd = top ? 0x88888888u : 0u;
     return c;
 }
 
@@ -173,16 +179,24 @@ __device__ __forceinline__ int lane_column(int L)
 }
 
 // Transposed digits of the two half words (columns 0-15, 16-31) -> the four A-operand registers
-// (register r, nibble n = digit of column 4 n + r, FP4 code = the digit).  `flip` turns the digits of x_q into
-// those of x' = x_q + 2^31: the upper bit of digit 15.
-__device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, uint32_t flip, u32x4 &dst)
+// (register r, nibble n = digit of column 4 n + r).  FP4 code = the digit (value digit / 2), except for the
+// signed digit 15, whose values 0, 1, -2, -1 are the codes 0000, 0001, 1010, 1001: bit 3 = b31, bit 1 = b31 & ~b30,
+// bit 0 = b30.
+__device__ __forceinline__ void digit_operand_pair(uint32_t m, const TransposeConsts &c, uint32_t &even, uint32_t &odd)
+{
+    // m holds two digits per nibble: bits 1, 0 (-> `even`) and bits 3, 2 (-> `odd`)
+    const uint32_t u = m & ~((m << 1) & c.top_hi);      // top digit: upper bit cleared where the lower one is set
+    even = (u & 0x33333333u) | ((m & c.top_hi_even) << 2);
+    odd = ((u >> 2) & 0x33333333u) | (m & c.top_hi_odd);
+}
+__device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, const TransposeConsts &c, u32x4 &dst)
 {
     const uint32_t m0 = __builtin_amdgcn_perm(q, p, 0x05040100u);   // low halves of p and q
     const uint32_t m1 = __builtin_amdgcn_perm(q, p, 0x07060302u);   // high halves
-    dst.x = (m0 & 0x33333333u) ^ flip;
-    dst.y = ((m0 >> 2) & 0x33333333u) ^ flip;
-    dst.z = (m1 & 0x33333333u) ^ flip;
-    dst.w = ((m1 >> 2) & 0x33333333u) ^ flip;
+    uint32_t r0, r1, r2, r3;
+    digit_operand_pair(m0, c, r0, r1);
+    digit_operand_pair(m1, c, r2, r3);
+    dst = u32x4{r0, r1, r2, r3};
 }
 
 // The same operand from the two plane words (bit c = column c) of a digit row: p0 the lower plane, p1 the upper
@@ -196,6 +210,13 @@ __device__ __forceinline__ void digit_operand_from_planes(uint32_t p0, uint32_t 
     dst.y = o & 0x33333333u;
     dst.z = (e >> 2) & 0x33333333u;
     dst.w = (o >> 2) & 0x33333333u;
+}
+
+// digits (b1 b0) of the top row -> the codes of their signed value -2 b1 + b0; `top` = 0x22222222 in the lanes
+// of digit 15, else 0 (then nothing changes)
+__device__ __forceinline__ uint32_t signed_top_digit(uint32_t d, uint32_t top)
+{
+    return (d & ~((d << 1) & top)) | ((d & top) << 2);
 }
 
 __device__ __forceinline__ v8i as_operand(const u32x4 v)
@@ -315,12 +336,12 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     };
 
     // ---- the digit rows of this wave's slice, as A operands, kept in registers ----
-    // lane l = 16 * kb + i: digit i (planes 2 i, 2 i + 1 of x' = x_q ^ 2^31) of the words 16 * q + 4 * kb + t
+    // lane l = 16 * kb + i: digit i (planes 2 i, 2 i + 1 of x_q) of the words 16 * q + 4 * kb + t
     const int kb = lane >> 4;
     u32x4 pa[NV][NQ][4];
     constexpr int VG = NV > 4 ? 4 : NV;   // vectors whose activations are in flight together
     if (a.planes) {
-        const uint32_t flip = (lane & 15) == 15 ? 0xFFFFFFFFu : 0u;   // plane 31 of x' is the complement of x_q's
+        const uint32_t top = (lane & 15) == 15 ? 0x22222222u : 0u;
 #pragma unroll
         for (int g = 0; g < NV; g += VG) {
             uint4 pl0[VG][NQ], pl1[VG][NQ];
@@ -349,10 +370,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     const uint4 p0 = pl0[v][q], p1 = pl1[v][q];
-                    digit_operand_from_planes(p0.x, p1.x ^ flip, pa[g + v][q][0]);
-                    digit_operand_from_planes(p0.y, p1.y ^ flip, pa[g + v][q][1]);
-                    digit_operand_from_planes(p0.z, p1.z ^ flip, pa[g + v][q][2]);
-                    digit_operand_from_planes(p0.w, p1.w ^ flip, pa[g + v][q][3]);
+                    digit_operand_from_planes(p0.x, p1.x, pa[g + v][q][0]);
+                    digit_operand_from_planes(p0.y, p1.y, pa[g + v][q][1]);
+                    digit_operand_from_planes(p0.z, p1.z, pa[g + v][q][2]);
+                    digit_operand_from_planes(p0.w, p1.w, pa[g + v][q][3]);
+#pragma unroll
+                    for (int t = 0; t < 4; ++t)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) pa[g + v][q][t][r] = signed_top_digit(pa[g + v][q][t][r], top);
                 }
         }
     } else {
@@ -433,8 +458,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                             (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][1]), a.fscale, a.imin, a.imax);
                         const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
                         // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
-                        digit_operand(digit_transpose16(sw[0], tc), digit_transpose16(sw[1], tc), tc.flip,
-                                      pa[g + v][q][t]);
+                        digit_operand(digit_transpose16(sw[0], tc), digit_transpose16(sw[1], tc), tc, pa[g + v][q][t]);
                     }
         }
     }
@@ -451,7 +475,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
     // per-lane digit weights: register c holds digit 4 kb + c, which weighs 4^(4 kb + c); lanes kb = 0, 1 sum
-    // digits 0-7 (bits 0-15 of x') in units of 1, lanes kb = 2, 3 digits 8-15 in units of 2^16
+    // digits 0-7 (bits 0-15 of x_q) in units of 1, lanes kb = 2, 3 digits 8-15 (the signed upper half) in units of 2^16
     // (the products are digit * 1 bitlayer by bitlayer and digit * digit / 4 with merged pairs)
     float kw[4];
 #pragma unroll
@@ -473,23 +497,19 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc);
             const float f = acc[0] * kw[0] + acc[1] * kw[1] + acc[2] * kw[2] + acc[3] * kw[3];
-            sx[v] = (int)f - (half ? (256 * NQ) << 15 : 0);   // x_q = x' - 2^31 in each of the 512 NQ columns
+            sx[v] = (int)f;
         }
     }
     int pp = 0, pr = 0;   // pair and round of the unit being multiplied
-    // the end of a pass: sd = sum of the weight digits of this lane's words (row j, k-block kb), `set` = its sums in LDS
-    auto finish = [&](const v4f (&acc)[NV], int sd, int set, bool sign_pair) {
-        // sum w x_q = sum w x' - 2^31 * sum w.  The lanes of the upper half (units of 2^16) subtract 2^15 times
-        // the digit sum of their own k-block and of the one 32 lanes below.
-        const auto sds = __builtin_amdgcn_permlane32_swap((uint32_t)sd, (uint32_t)sd, false, false);
-        const int corr = half ? (int)((sds[0] + sds[1]) << 15) : 0;
-        // digit weighting inside the lane.  Sums of digit products are <= 9 * 2048 (a slice has at most 2048
-        // columns), so c0 + 4 c1 + 16 c2 + 64 c3 < 2^21 and its multiple by 2^8 is exact in fp32 and < 2^29.
+    // the end of a pass: the sums of this lane go to `set` in LDS
+    auto finish = [&](const v4f (&acc)[NV], int set, bool sign_pair) {
+        // digit weighting inside the lane.  Sums of digit products are <= 9 * 2048 in magnitude (a slice has at
+        // most 2048 columns), so c0 + 4 c1 + 16 c2 + 64 c3 < 2^21 and its multiple by 2^8 is exact in fp32, < 2^29.
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             const float f = acc[v][0] * kw[0] + acc[v][1] * kw[1] + acc[v][2] * kw[2] + acc[v][3] * kw[3];
             // (the digits of the sign pair stand 2 too high in every column)
-            atomicAdd(&abuf[pr & 1][v][set][half][j], (int)f - corr - (sign_pair ? 2 * sx[v] : 0));
+            atomicAdd(&abuf[pr & 1][v][set][half][j], (int)f - (sign_pair ? 2 * sx[v] : 0));
         }
     };
     for (int u0 = 0; u0 < U; u0 += RU) {
@@ -503,7 +523,6 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                     v4f acc[NV];
 #pragma unroll
                     for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
-                    int pcl = 0, pch = 0;
                     const bool sign_pair = pp == 0 && has_hi;
                     const uint32_t inv = sign_pair ? 0xFFFFFFFFu : 0u;   // the sign bitlayer enters as 1 - w
 #pragma unroll
@@ -512,13 +531,11 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
                             const v8i b = weight_digit_operand(wh[t], wl[t]);
-                            pcl += __builtin_popcount(wl[t]);
-                            pch += __builtin_popcount(wh[t]);
 #pragma unroll
                             for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
                         }
                     }
-                    finish(acc, 2 * pch + pcl, pp, sign_pair);
+                    finish(acc, pp, sign_pair);
                 } else {
 #pragma unroll
                     for (int h = PAIR ? 1 : 0; h >= 0; --h) {
@@ -526,19 +543,17 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         v4f acc[NV];
 #pragma unroll
                         for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
-                        int pc = 0;
 #pragma unroll
                         for (int q = 0; q < NQ; ++q) {
                             const u32x4 w = ring[k][h * NQ + q];
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
                                 const v8i b = weight_operand(w[t]);
-                                pc += __builtin_popcount(w[t]);
 #pragma unroll
                                 for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
                             }
                         }
-                        finish(acc, pc, lo_layer - h, false);
+                        finish(acc, lo_layer - h, false);
                     }
                 }
                 if (++pp == mp) {
