@@ -193,18 +193,20 @@ def test_reduced_activation_precision(pb, layout):
         run_layer(pb, W, 4, X, [2, 4], frac_bits=f, act_bits=k, layout=layout)
 
 
-def test_prepared_halves_equal_whole_call(pb, layout):
+@pytest.mark.parametrize("fmt", [(32, 16, 2, "normal"), (8, 4, 1, "wide"), (16, 12, 5, "wide"), (32, 16, 9, "wide")])
+def test_prepared_halves_equal_whole_call(pb, layout, fmt):
     """pb_act_prep + pb_matmul_prepared (planes through memory) against pb_matmul and the oracle."""
-    W, X = synth.ragged(150, 2100, batch=2, case=7, xdist="normal")
+    act_bits, frac_bits, N, xdist = fmt
+    W, X = synth.ragged(150, 2100, batch=N, case=7, xdist=xdist)
     bits, m = 6, 5
-    lin = pb.PackedLinear(dev(W), bits, max_batch=2, layout=layout)
-    ref = oracle_reference(W, bits, X, m)
+    lin = pb.PackedLinear(dev(W), bits, max_batch=N, layout=layout, frac_bits=frac_bits, act_bits=act_bits)
+    ref = oracle_reference(W, bits, X, m, frac_bits=frac_bits, act_bits=act_bits)
     Xd = dev(X)
     Y1 = lin(Xd, m).cpu().numpy()
-    Y2 = torch.empty((2, 150), dtype=torch.float32, device="cuda")
-    pb.pb_act_prep(lin.desc, Xd, 2, lin.workspace)
-    pb.pb_matmul_prepared(lin.packed, lin.scales, lin.desc, m, 2, Y2, lin.workspace)
-    assert_y_close(Y1, ref["Y"], ref["A"], ref["scales"])
+    Y2 = torch.empty((N, 150), dtype=torch.float32, device="cuda")
+    pb.pb_act_prep(lin.desc, Xd, N, lin.workspace)
+    pb.pb_matmul_prepared(lin.packed, lin.scales, lin.desc, m, N, Y2, lin.workspace)
+    assert_y_close(Y1, ref["Y"], ref["A"], ref["scales"], frac_bits=frac_bits)
     assert (Y2.cpu().numpy().view(np.int32) == Y1.view(np.int32)).all()
 
 
