@@ -52,7 +52,8 @@ typedef enum pb_status {
 /* Packed layouts (opaque to the caller; pb_unpack reads either).
  * PB_LAYOUT_TILE16_V1   16-row x 512-column blocks in the order the matrix-core kernel streams them; the
  *                       default wherever it applies (cols <= 16384).  The product runs as FP4 matrix
- *                       instructions on the 0/1 bitlayers and planes, exact in fp32 accumulators.
+ *                       instructions on the bitlayers and planes (two of each per operand element, as
+ *                       base-4 digits), exact in fp32 accumulators.
  * PB_LAYOUT_ROWMAJOR_V1 [bitlayer][row][word]; read by the AND + popcount kernel (Section 3.4 taken
  *                       literally), kept as the measured alternative and for cols up to PB_MAX_COLS. */
 #define PB_LAYOUT_ROWMAJOR_V1 0x50420001u
