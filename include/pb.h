@@ -51,11 +51,11 @@ typedef enum pb_status {
 
 /* Packed layouts (opaque to the caller; pb_unpack reads either).
  * PB_LAYOUT_TILE16_V1   16-row x 512-column blocks in the order the matrix-core kernel streams them; the
- *                       default wherever it applies (cols <= 16384).  The product runs as FP4 matrix
+ *                       default.  The product runs as FP4 matrix
  *                       instructions on the bitlayers and planes (two of each per operand element, as
  *                       base-4 digits), exact in fp32 accumulators.
  * PB_LAYOUT_ROWMAJOR_V1 [bitlayer][row][word]; read by the AND + popcount kernel (Section 3.4 taken
- *                       literally), kept as the measured alternative and for cols up to PB_MAX_COLS. */
+ *                       literally), kept as the measured alternative. */
 #define PB_LAYOUT_ROWMAJOR_V1 0x50420001u
 #define PB_LAYOUT_TILE16_V1 0x50420002u
 /* PB_LAYOUT_TILE16_GATES_V1  the tiled layout for the fused gate matrix of an LSTM (rows = 4H, gate order
@@ -174,7 +174,8 @@ int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const flo
  * bits_used is 1), P[p] = 2 A_(2p) + A_(2p+1), P[last] = A_(bits_used-1) for a
  * single one.
  * A: [(bits_used + 1) / 2][batch][rows] int64, written.  Tiled layouts only
- * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1).  pb_matmul with more than one vector
+ * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1) and cols <= 16384 (PB_ESIZE beyond: wider
+ * matrices are multiplied bitlayer by bitlayer, the pair sums would not fit).  pb_matmul with more than one vector
  * takes this route by itself when scales[0] == -2 * scales[1] and scales[2p] ==
  * 2 * scales[2p + 1] hold for every pair, else it multiplies bitlayer by
  * bitlayer. */

@@ -55,8 +55,7 @@ int pb_desc_init_layout(pb_desc *d, int rows, int cols, int bits, uint32_t layou
 
 int pb_desc_init(pb_desc *d, int rows, int cols, int bits)
 {
-    return pb_desc_init_layout(d, rows, cols, bits,
-                               cols <= pb::kMaxColsTile16 ? PB_LAYOUT_TILE16_V1 : PB_LAYOUT_ROWMAJOR_V1);
+    return pb_desc_init_layout(d, rows, cols, bits, PB_LAYOUT_TILE16_V1);
 }
 
 size_t pb_packed_bytes(const pb_desc *d)
@@ -125,6 +124,7 @@ static int matmul_common(const void *packed, const float *scales, const pb_desc 
         return PB_EALIGN;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (ep.bias && !aligned16(ep.bias)) return PB_EALIGN;
+    if (pairs_out && L.cols > pb::kMaxColsPairs) return PB_ESIZE;
     if (pb::is_tile16(L.layout))   // conversion, bit transpose, product and epilogue in one launch
         return hip_status(pb::launch_mfma(static_cast<const uint32_t *>(packed), scales, L, bits_used, d->frac_bits,
                                           d->act_bits, X0, cols0, X1, cols1, nullptr, batch, Y,

@@ -39,7 +39,8 @@ constexpr int kMetaInts = 16;       // per activation vector, in the workspace
 constexpr int kTileRows = 16;       // matrix-core kernel: rows per tile
 constexpr int kChunkWords = 16;     // matrix-core kernel: words per row in one block
 constexpr int kMaxSlices = 16;      // matrix-core kernel: waves (column slices) per workgroup
-constexpr int kMaxColsTile16 = 16384;
+constexpr int kMaxColsTile16 = 32768;     // 16 slices of 2048 columns
+constexpr int kMaxColsPairs = 16384;      // merged bitlayer pairs: their sums of digit products up to 9 fit 32 bits
 
 struct Layout {
     uint32_t layout;

@@ -646,6 +646,7 @@ static const Variant kVariants[] = {
     PB_VARIANT(2, 2, 8, 1),  PB_VARIANT(2, 2, 8, 2),
     PB_VARIANT(2, 4, 8, 1),  PB_VARIANT(2, 4, 8, 2),
     PB_VARIANT(4, 1, 8, 1),  PB_VARIANT(4, 1, 8, 2),
+    PB_VARIANT(4, 1, 16, 1),
     PB_VARIANT(4, 2, 8, 1),  PB_VARIANT(4, 2, 8, 2),
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
@@ -692,7 +693,7 @@ static int pick_ring(int vi, int units)
     int best = vi;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
-        if (v.nq != kVariants[vi].nq || v.nv != kVariants[vi].nv) continue;
+        if (v.nq != kVariants[vi].nq || v.nv != kVariants[vi].nv || v.maxs != kVariants[vi].maxs) continue;
         if (want ? v.ru == want : (v.ru <= units && v.ru > kVariants[best].ru)) best = i;
     }
     return best;
@@ -747,6 +748,10 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     // Bitlayer pairs when several vectors share the expanded weights (and for the parity hook of the pairs)
     bool pair = a.pairs_out || (!A && batch >= 2);
     if (tuning().pair >= 0) pair = a.pairs_out || (!A && tuning().pair != 0);
+    if (L.cols > kMaxColsPairs) {
+        if (a.pairs_out) return (int)hipErrorInvalidValue;   // (the host API rejects this before)
+        pair = false;
+    }
     int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S, pair);   // of the sibling that needs the most registers
     if (capacity < 1) return (int)hipErrorInvalidValue;
     if (tuning().wgs > 0) capacity = tuning().wgs;

@@ -53,11 +53,9 @@ def test_desc_and_sizes(pb):
     assert pb.pb_packed_bytes(d) == 3 * 100 * 96 * 4
     d = pb.pb_desc_init_layout(10, 784, 2, pb.PB_LAYOUT_ROWMAJOR_V1)
     assert pb.pb_packed_bytes(d) == 2 * 12 * 32 * 4
-    # the tiled layout stops at 16384 columns; wider matrices get the row-major one
-    assert pb.pb_desc_init(8, 16385, 2).layout == pb.PB_LAYOUT_ROWMAJOR_V1
-    with pytest.raises(pb.PbError) as e:
-        pb.pb_desc_init_layout(8, 16385, 2, pb.PB_LAYOUT_TILE16_V1)
-    assert e.value.status == pb.PB_ESIZE
+    # the tiled layout is the default at every width
+    assert pb.pb_desc_init(8, pb.PB_MAX_COLS, 2).layout == pb.PB_LAYOUT_TILE16_V1
+    assert pb.pb_packed_bytes(pb.pb_desc_init(8, 16385, 2)) == 2 * 16 * 528 * 4
     with pytest.raises(pb.PbError) as e:
         pb.pb_desc_init_layout(8, 64, 2, 7)
     assert e.value.status == pb.PB_EINVAL
@@ -155,6 +153,8 @@ def test_pair_hook_and_calibration_arguments_rejected_before_launch(pb):
     assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 4, fake, 1, null, fake, null) == pb.PB_EINVAL    # A null
     assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 0, fake, 1, fake, fake, null) == pb.PB_EINVAL    # bits_used
     assert L.pb_matmul_acc_pairs(fake, ctypes.byref(d), 4, fake, 0, fake, fake, null) == pb.PB_EINVAL    # batch
+    wide = pb.pb_desc_init(16, 16385, 4)    # pair sums of more than 16384 columns would not fit 32-bit halves
+    assert L.pb_matmul_acc_pairs(fake, ctypes.byref(wide), 4, fake, 1, fake, fake, null) == pb.PB_ESIZE
     for mode, iters, wgs, out in ((3, 1, 1, fake), (-1, 1, 1, fake), (0, 0, 1, fake), (0, 1, 0, fake),
                                   (0, 1, 1, null), (0, (1 << 20) + 1, 1, fake), (0, 1, 65537, fake)):
         assert L.pb_calib_mfma(mode, iters, wgs, out, null) == pb.PB_EINVAL
