@@ -253,7 +253,8 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 // RU <= the units a wave has, so that a short stream pays for no empty ring slots; 4 KB in flight per wave
 // measured best (more requests in flight than that slow the short streams down and do not speed up the long ones).
 // PAIR: a unit is a pair of bitlayers (worth it when several vectors share the expanded weights; with one vector
-// the half-empty units of the single bitlayers cost more than the saved instructions).
+// it measured 5-10 % slower up to 8192 columns and the same beyond: the stream starts later and a call has too few
+// units for the saved instructions to show).
 template <int NQ, int NV, int MAXS, int RU, bool PAIR>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 {
