@@ -124,80 +124,41 @@ __device__ __forceinline__ double add_across(double z)
            __longlong_as_double((long long)(((unsigned long long)h[1] << 32) | l[1]));
 }
 
-// Per-lane constants of the 16 x 16 transpose of 2-bit digits across a row of 16 lanes: lane L enters with the 32-bit
-// value of one column, lane i leaves with digit i (bits 2 i, 2 i + 1) of the 16 columns, the digit of the column
-// that entered in lane L at bits 2 L, 2 L + 1.  In stage J lanes l and l ^ J exchange the digit positions that have
-// bit J set (lower lane) / clear (upper lane); keep = the positions a lane keeps, rot = right-rotation that moves
-// the partner's digits into the others (>> 2 J for the upper lane, << 2 J for the lower).
-struct TransposeConsts {
-    uint32_t sel8, sel4;            // byte selectors of the stages that move whole bytes
-    uint32_t keep2, keep1;
-    uint32_t rot2, rot1;
-    // digit 15 is the signed one (bits 31, 30 of the value: -2 b31 + b30): the positions of its bits in a word of
-    // the transpose, non-zero in the lanes of digit 15 only
-    uint32_t top_hi;                // 0xAAAAAAAA: the upper bit of every digit
-    uint32_t top_hi_even, top_hi_odd;   // 0x22222222, 0x88888888: the same, digits at even / odd positions
-};
+// Row order of the A operand.  The sixteen base-4 digits of a value travel as FP4 codes in two words, bytes
+// [x.b0 & 0x33, (x >> 2).b0 & 0x33, x.b1 & 0x33, ...]: nibble i of the pair holds digit kDigitOfRow(i), the order
+// 0 2 1 3 | 4 6 5 7 | 8 10 9 11 | 12 14 13 15 (bits 0 and 1 of the index exchanged).  Operand row i = that nibble,
+// so four consecutive rows (the four registers of a lane of the result) still hold four consecutive digits.
+__device__ __forceinline__ int digit_of_row(int i) { return (i & 12) | ((i & 1) << 1) | ((i >> 1) & 1); }
 
-__device__ __forceinline__ TransposeConsts transpose_consts(int lane)
+// x_q (k-bit two's complement, sign-extended) -> the FP4 codes of its sixteen digits, nibble i = digit
+// digit_of_row(i); code = digit (value digit / 2), except for digit 15, the signed one (-2 b31 + b30: values
+// 0, 1, -2, -1 = codes 0000, 0001, 1010, 1001), which a byte table indexed by the two top bits supplies.
+__device__ __forceinline__ uint2 digit_codes(uint32_t x)
 {
-    TransposeConsts c;
-    c.sel8 = (lane & 8) ? 0x03020706u : 0x05040100u;   // (partner's, own) bytes 4-7, 0-3: halves exchanged
-    c.sel4 = (lane & 4) ? 0x03070105u : 0x06020400u;   // bytes exchanged
-    c.keep2 = (lane & 2) ? 0xF0F0F0F0u : 0x0F0F0F0Fu; c.rot2 = (lane & 2) ? 4 : 28;
-    c.keep1 = (lane & 1) ? 0xCCCCCCCCu : 0x33333333u; c.rot1 = (lane & 1) ? 2 : 30;
-    const bool top = (lane & 15) == 15;
-    c.top_hi = top ? 0xAAAAAAAAu : 0u;
-    c.top_hi_even = top ? 0x22222222u : 0u;
-    c.top_hi_odd = top ? 0x88888888u : 0u;
-    return c;
+    const uint32_t s = x >> 2;
+    const uint32_t g0 = __builtin_amdgcn_perm(s, x, 0x05010400u) & 0x33333333u;   // bytes x.b0, s.b0, x.b1, s.b1
+    const uint32_t g1 = __builtin_amdgcn_perm(s, x, 0x07030602u) & 0x33333333u;   // bytes x.b2, s.b2, x.b3, s.b3
+    // byte 3 of the selector x >> 6 is x >> 30: it picks the code (in the upper nibble) out of the table
+    const uint32_t top = __builtin_amdgcn_perm(0u, 0x90A01000u, x >> 6);
+    return make_uint2(g0, (g1 & 0x0FFFFFFFu) | (top & 0xF0000000u));
 }
 
-template <int J>
-__device__ __forceinline__ uint32_t transpose_stage(uint32_t x, uint32_t keep, uint32_t rot)
+// The 16 x 16 transpose of 4-bit elements that the LDS performs on a read (DS_READ_B64_TR_B4): in every group of
+// 16 lanes, lane i receives nibble i of the 64-bit rows that the lanes e = 0 .. 15 of its group address, the one
+// of lane e in nibble e.
+typedef int v2i __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint2 lds_read_transposed(const uint2 *row)
 {
-    const uint32_t other = row_xor<J>(x);
-    const uint32_t moved = __builtin_amdgcn_alignbit(other, other, rot);
-    return (x & keep) | (moved & ~keep);
+    const v2i r = __builtin_amdgcn_ds_read_tr4_b64_v2i32((v2i __attribute__((address_space(3))) *)(row));
+    return make_uint2((uint32_t)r.x, (uint32_t)r.y);
 }
 
-__device__ __forceinline__ uint32_t digit_transpose16(uint32_t x, const TransposeConsts &c)
-{
-    x = __builtin_amdgcn_perm(row_xor<8>(x), x, c.sel8);
-    x = __builtin_amdgcn_perm(row_xor<4>(x), x, c.sel4);
-    x = transpose_stage<2>(x, c.keep2, c.rot2);
-    x = transpose_stage<1>(x, c.keep1, c.rot1);
-    return x;
-}
-
-// The column that lane L of a row converts, among the 16 of its half word: with this order the transposed word has
-// the digit of column 4 n + r (of the half word) at bits 4 n + 2 (r & 1) + 16 (r >> 1), which the A operand needs
-// at bits 4 n of register r.
-__device__ __forceinline__ int lane_column(int L)
-{
-    return (L & 1) | ((L >> 2) & 2) | ((L << 1) & 4) | ((L << 1) & 8);
-}
-
-// Transposed digits of the two half words (columns 0-15, 16-31) -> the four A-operand registers
-// (register r, nibble n = digit of column 4 n + r).  FP4 code = the digit (value digit / 2), except for the
-// signed digit 15, whose values 0, 1, -2, -1 are the codes 0000, 0001, 1010, 1001: bit 3 = b31, bit 1 = b31 & ~b30,
-// bit 0 = b30.
-__device__ __forceinline__ void digit_operand_pair(uint32_t m, const TransposeConsts &c, uint32_t &even, uint32_t &odd)
-{
-    // m holds two digits per nibble: bits 1, 0 (-> `even`) and bits 3, 2 (-> `odd`)
-    const uint32_t u = m & ~((m << 1) & c.top_hi);      // top digit: upper bit cleared where the lower one is set
-    even = (u & 0x33333333u) | ((m & c.top_hi_even) << 2);
-    odd = ((u >> 2) & 0x33333333u) | (m & c.top_hi_odd);
-}
-__device__ __forceinline__ void digit_operand(uint32_t p, uint32_t q, const TransposeConsts &c, u32x4 &dst)
-{
-    const uint32_t m0 = __builtin_amdgcn_perm(q, p, 0x05040100u);   // low halves of p and q
-    const uint32_t m1 = __builtin_amdgcn_perm(q, p, 0x07060302u);   // high halves
-    uint32_t r0, r1, r2, r3;
-    digit_operand_pair(m0, c, r0, r1);
-    digit_operand_pair(m1, c, r2, r3);
-    dst = u32x4{r0, r1, r2, r3};
-}
+// Staging area of one wave for one chunk of 512 columns: 16 words x 32 columns x 8 bytes (the codes of a column).
+// The row of column 4 n + r of word w sits at w * 32 + ((r + rot(w)) & 3) * 8 + n (in units of 8 bytes): the
+// columns of one operand register are contiguous, and the rotation spreads the lanes of a write (eight words,
+// the same n) and of a read (four words, 128 bytes each) over the banks.
+constexpr int kStageRows = 512;
+__device__ __forceinline__ int stage_row(int w, int r, int n) { return w * 32 + (((r + w + (w >> 2)) & 3) << 3) + n; }
 
 // The same operand from the two plane words (bit c = column c) of a digit row: p0 the lower plane, p1 the upper
 __device__ __forceinline__ void digit_operand_from_planes(uint32_t p0, uint32_t p1, u32x4 &dst)
@@ -268,6 +229,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     // used by alternate row tiles
     __shared__ int abuf[2][NV][PB_MAX_BITS][2][kTileRows];
     __shared__ float s_scales[PB_MAX_BITS];
+    // staging area of the activation transpose, kStageRows rows of 8 bytes per wave (none when the planes are given)
+    extern __shared__ __align__(16) unsigned char stage_lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -351,7 +314,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 const int n = min(n0 + g + v, a.batch - 1);
                 const bool live = n0 + g + v < a.batch;
                 const uint32_t *pl =
-                    a.planes + ((size_t)n * 32 + 2 * (lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
+                    a.planes + ((size_t)n * 32 + 2 * digit_of_row(lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     pl0[v][q] = pl1[v][q] = make_uint4(0, 0, 0, 0);
@@ -382,18 +345,20 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 }
         }
     } else {
-        // Algorithm 2: x_q = Int(x * 2^f); then the transpose, 32 columns x 16 digits at a time in each half of
-        // the wave: lane (half H, c) converts one column of the words 16 q + 4 (2 H + e) + t, e = 0, 1.
-        // V_PERMLANE16_SWAP hands the even rows of 16 lanes both 16-column halves of the e = 0 word and the odd
-        // rows those of the e = 1 word; the four exchange stages stay inside a row.  Lane (kb, i) ends with digit
-        // i of the 32 columns of word 16 q + 4 kb + t.
-        // Buffer loads return 0 beyond the end of a vector, and for the vectors beyond the end of the batch.
-        const int colb = (32 * (16 * q0 + 8 * (lane >> 5)) + (lane & 16) + lane_column(lane & 15)) * 4;
-        const int colb1 = colb - a.cols0 * 4;
-        const TransposeConsts tc = transpose_consts(lane);
+        // Algorithm 2: x_q = Int(x * 2^f); then the transpose of Section 3.4 through LDS.  Lane L loads the
+        // columns 256 j + 4 L .. + 3 (j = 0, 1) of a chunk with one 16-byte load each, converts them, writes the
+        // sixteen digit codes of every column as one 8-byte row into this wave's staging area and reads the rows back
+        // transposed: lane (kb, i) receives digit row i of the 32 columns of word 4 kb + t, register r = the
+        // columns 4 n + r, which is the A operand as it stands.
+        // Buffer loads return 0 beyond the end of a vector (checked dword by dword), and for the vectors beyond the
+        // end of the batch.
+        uint2 *stage = reinterpret_cast<uint2 *>(stage_lds) + wave * kStageRows;
+        const int wr_n = lane & 7, wr_w = lane >> 3;          // a load's four columns: word 8 j + wr_w, n = wr_n
+        const int rd_e = lane & 15;
+        const int col0 = 512 * q0 + 4 * lane;                 // first column of the lane's load j = 0 of chunk 0
 #pragma unroll
         for (int g = 0; g < NV; g += VG) {
-            uint32_t xv[VG][NQ][4][2];
+            u32x4 xv[VG][NQ][2];
 #pragma unroll
             for (int v = 0; v < VG; ++v) {
                 const int n = min(n0 + g + v, a.batch - 1);
@@ -403,17 +368,15 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                    for (int t = 0; t < 4; ++t)
-#pragma unroll
-                        for (int e = 0; e < 2; ++e)
-                            xv[v][q][t][e] =
-                                __builtin_amdgcn_raw_buffer_load_b32(rx0, colb + 128 * (16 * q + 4 * e + t), 0, 0);
+                    for (int j = 0; j < 2; ++j)
+                        xv[v][q][j] = __builtin_amdgcn_raw_buffer_load_b128(rx0, (col0 + 512 * q + 256 * j) * 4, 0, 0);
             }
-            // Second part of a concatenated input [X0 ; X1]: at most one of the two loads of a column is in range.
-            // Columns of the first part would have negative offsets here; those are clamped and the value dropped
-            // (a negative register offset that an instruction offset brings back above zero is not range-checked
-            // lane by lane on this hardware).
-            uint32_t xw[VG][NQ][4][2];
+            // Second part of a concatenated input [X0 ; X1].  Offsets of columns that belong to the first part
+            // would be negative: they are clamped and the value dropped (a negative register offset that an
+            // instruction offset brings back above zero is not range-checked lane by lane on this hardware).
+            // If cols0 is a multiple of 4 a lane's four columns lie in one part and one 16-byte load serves;
+            // else every column is loaded by itself.
+            u32x4 xw[VG][NQ][2];
             if (a.X1) {
 #pragma unroll
                 for (int v = 0; v < VG; ++v) {
@@ -424,11 +387,16 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                     for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
+                        for (int j = 0; j < 2; ++j) {
+                            const int c1 = col0 + 512 * q + 256 * j - a.cols0;
+                            if ((a.cols0 & 3) == 0) {
+                                xw[v][q][j] = __builtin_amdgcn_raw_buffer_load_b128(rx1, max(c1, 0) * 4, 0, 0);
+                            } else {
 #pragma unroll
-                            for (int e = 0; e < 2; ++e)
-                                xw[v][q][t][e] = __builtin_amdgcn_raw_buffer_load_b32(
-                                    rx1, max(colb1 + 128 * (16 * q + 4 * e + t), 0), 0, 0);
+                                for (int r = 0; r < 4; ++r)
+                                    xw[v][q][j][r] = __builtin_amdgcn_raw_buffer_load_b32(rx1, max(c1 + r, 0) * 4, 0, 0);
+                            }
+                        }
                 }
             }
             if (g == 0) {
@@ -442,25 +410,37 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
                     for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                        for (int t = 0; t < 4; ++t)
+                        for (int j = 0; j < 2; ++j)
 #pragma unroll
-                            for (int e = 0; e < 2; ++e)
-                                xv[v][q][t][e] |= colb1 + 128 * (16 * q + 4 * e + t) >= 0 ? xw[v][q][t][e] : 0u;
+                            for (int r = 0; r < 4; ++r)
+                                xv[v][q][j][r] |= col0 + 512 * q + 256 * j + r >= a.cols0 ? xw[v][q][j][r] : 0u;
             }
 #pragma unroll
             for (int v = 0; v < VG; ++v)
 #pragma unroll
-                for (int q = 0; q < NQ; ++q)
+                for (int q = 0; q < NQ; ++q) {
+                    // (the reads of the chunk before have returned: their registers were waited for below)
+#pragma unroll
+                    for (int j = 0; j < 2; ++j)
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) {
+                            const uint32_t xq =
+                                (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][j][r]), a.fscale, a.imin, a.imax);
+                            stage[stage_row(8 * j + wr_w, r, wr_n)] = digit_codes(xq);
+                        }
+                    // the wave's own writes have landed before its lanes read each other's rows
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_wave_barrier();
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        const uint32_t X =
-                            (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][0]), a.fscale, a.imin, a.imax);
-                        const uint32_t Y =
-                            (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][t][1]), a.fscale, a.imin, a.imax);
-                        const auto sw = __builtin_amdgcn_permlane16_swap(X, Y, false, false);
-                        // even rows: (columns 0-15, columns 16-31) of the e = 0 word; odd rows: of the e = 1 word
-                        digit_operand(digit_transpose16(sw[0], tc), digit_transpose16(sw[1], tc), tc, pa[g + v][q][t]);
+                        const uint2 lo = lds_read_transposed(stage + stage_row(4 * kb + t, rd_e >> 3, rd_e & 7));
+                        const uint2 hi = lds_read_transposed(stage + stage_row(4 * kb + t, 2 + (rd_e >> 3), rd_e & 7));
+                        pa[g + v][q][t] = u32x4{lo.x, lo.y, hi.x, hi.y};
                     }
+                    // ... and the reads have returned before the next chunk overwrites the rows
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                    __builtin_amdgcn_wave_barrier();
+                }
         }
     }
     if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
@@ -475,12 +455,13 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
-    // per-lane digit weights: register c holds digit 4 kb + c, which weighs 4^(4 kb + c); lanes kb = 0, 1 sum
-    // digits 0-7 (bits 0-15 of x_q) in units of 1, lanes kb = 2, 3 digits 8-15 (the signed upper half) in units of 2^16
+    // per-lane digit weights: register c holds operand row 4 kb + c = digit d = digit_of_row(4 kb + c), which weighs
+    // 4^d; lanes kb = 0, 1 sum digits 0-7 (bits 0-15 of x_q) in units of 1, lanes kb = 2, 3 digits 8-15 (the signed
+    // upper half) in units of 2^16
     // (the products are digit * 1 bitlayer by bitlayer and digit * digit / 4 with merged pairs)
     float kw[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * c + 8 * (kb & 1) + (merged ? 2 : 0)));
+    for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * (digit_of_row(4 * kb + c) & 7) + (merged ? 2 : 0)));
 
     const int j = lane & 15, half = lane >> 5;
     // sum_c x_q[c] over the slice, as this lane's share of it in the form the sums below have (merged pairs only):
@@ -700,6 +681,9 @@ static int pick_ring(int vi, int units)
     return best;
 }
 
+// Dynamic LDS of a workgroup of S waves: the staging area of the activation transpose.
+static size_t stage_bytes(int S) { return (size_t)S * kStageRows * sizeof(uint2); }
+
 // Workgroups of S waves that fit on the device at once (occupancy does not change while the process lives, so it
 // is looked up once per kernel variant and workgroup size).
 static int resident_workgroups(int variant, int S, bool pair)
@@ -712,7 +696,7 @@ static int resident_workgroups(int variant, int S, bool pair)
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &per_cu, pair ? kVariants[variant].fn_pair : kVariants[variant].fn, S * 64, 0) != hipSuccess)
+            &per_cu, pair ? kVariants[variant].fn_pair : kVariants[variant].fn, S * 64, stage_bytes(S)) != hipSuccess)
         return 0;
     v = cus * per_cu;
     if (v > 0) __atomic_store_n(slot, v, __ATOMIC_RELAXED);
@@ -763,8 +747,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
     void *args[] = {&a};
     const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used))];
-    const hipError_t e = hipLaunchKernel(pair ? run.fn_pair : run.fn, dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64), args,
-                                         0, st);
+    const hipError_t e = hipLaunchKernel(pair ? run.fn_pair : run.fn, dim3((unsigned)wgs, (unsigned)groups),
+                                         dim3((unsigned)S * 64), args, planes ? 0 : stage_bytes(S), st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
 }
 
