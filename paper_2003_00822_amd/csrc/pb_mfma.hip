@@ -57,9 +57,24 @@ typedef int v8i __attribute__((ext_vector_type(8)));
 typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-struct MfmaArgs {
+// The arguments that the first memory requests of a wave depend on are the kernel's leading scalar parameters: those
+// (fourteen dwords) the hardware loads into registers before a wave starts (kernel-argument preload), so the requests
+// need not wait for a round trip to the argument buffer.  The rest travels as one structure.
+struct MfmaHead {
     const uint32_t *packed;
-    const float *X0, *X1;       // activations: row n is [X0[n][0..cols0) ; X1[n][0..cols1)]
+    const float *X0;            // activations: row n is [X0[n][0..cols0) ; X1[n][0..cols1)]
+    uint32_t packed_bytes;      // (below 2^32: the blocks are addressed with 32-bit offsets)
+    uint32_t flags;             // kPlanesGiven: bit planes already in memory (prepared mode); kSecondPart: X1 is given
+    int cols0;
+    int batch;
+    uint32_t layer_step, round_step;   // bytes from one bitlayer of a row tile to the next, from one row tile to the next
+    int rounds_per_wg;          // row tiles per workgroup
+    int rt_count, cq;
+    int m;                      // bitlayers to accumulate
+};
+constexpr uint32_t kPlanesGiven = 1, kSecondPart = 2;
+struct MfmaArgs {
+    const float *X1;
     const uint32_t *planes;     // non-null: bit planes already in memory [batch][32][cwp] (prepared mode)
     const float *scales;
     float *Y;
@@ -70,13 +85,8 @@ struct MfmaArgs {
     float *h_out, *c_out;
     int relu;                   // max(., 0) before the store of Y
     int gate_h;                 // gate-interleaved rows: H (packed row 16 t + 4 (u % 4) + gate = row gate * H + u), else 0
-    size_t packed_bytes;
-    uint32_t layer_step, round_step;   // bytes from one bitlayer of a row tile to the next, from one row tile to the next
-    int cols0, cols1;
-    int R, rt_count, cq, cwp;
-    int m;                      // bitlayers to accumulate
-    int batch;
-    int rounds_per_wg;          // row tiles per workgroup
+    int cols1;
+    int R, cwp;
     float fscale;               // 2^frac_bits
     int imin, imax;             // range of the act_bits-bit fixed-point values
     double out_scale;           // 2^-frac_bits
@@ -124,23 +134,22 @@ __device__ __forceinline__ double add_across(double z)
            __longlong_as_double((long long)(((unsigned long long)h[1] << 32) | l[1]));
 }
 
-// Row order of the A operand.  The sixteen base-4 digits of a value travel as FP4 codes in two words, bytes
-// [x.b0 & 0x33, (x >> 2).b0 & 0x33, x.b1 & 0x33, ...]: nibble i of the pair holds digit kDigitOfRow(i), the order
-// 0 2 1 3 | 4 6 5 7 | 8 10 9 11 | 12 14 13 15 (bits 0 and 1 of the index exchanged).  Operand row i = that nibble,
-// so four consecutive rows (the four registers of a lane of the result) still hold four consecutive digits.
-__device__ __forceinline__ int digit_of_row(int i) { return (i & 12) | ((i & 1) << 1) | ((i >> 1) & 1); }
+// Row order of the A operand.  The sixteen base-4 digits of a value travel as FP4 codes in two words: E = the even
+// digits (x & 0x33333333: nibble k = digit 2 k) and O = the odd ones ((x >> 2) & 0x33333333: nibble k = digit
+// 2 k + 1).  Operand row i is nibble i of the pair (E, O): rows 0-7 hold the digits 0, 2, .., 14 and rows 8-15 the
+// digits 1, 3, .., 15.
+__device__ __forceinline__ int digit_of_row(int i) { return ((i & 7) << 1) | (i >> 3); }
 
 // x_q (k-bit two's complement, sign-extended) -> the FP4 codes of its sixteen digits, nibble i = digit
 // digit_of_row(i); code = digit (value digit / 2), except for digit 15, the signed one (-2 b31 + b30: values
 // 0, 1, -2, -1 = codes 0000, 0001, 1010, 1001), which a byte table indexed by the two top bits supplies.
 __device__ __forceinline__ uint2 digit_codes(uint32_t x)
 {
-    const uint32_t s = x >> 2;
-    const uint32_t g0 = __builtin_amdgcn_perm(s, x, 0x05010400u) & 0x33333333u;   // bytes x.b0, s.b0, x.b1, s.b1
-    const uint32_t g1 = __builtin_amdgcn_perm(s, x, 0x07030602u) & 0x33333333u;   // bytes x.b2, s.b2, x.b3, s.b3
+    const uint32_t e = x & 0x33333333u;
+    const uint32_t o = (x >> 2) & 0x33333333u;
     // byte 3 of the selector x >> 6 is x >> 30: it picks the code (in the upper nibble) out of the table
     const uint32_t top = __builtin_amdgcn_perm(0u, 0x90A01000u, x >> 6);
-    return make_uint2(g0, (g1 & 0x0FFFFFFFu) | (top & 0xF0000000u));
+    return make_uint2(e, (o & 0x0FFFFFFFu) | (top & 0xF0000000u));
 }
 
 // The 16 x 16 transpose of 4-bit elements that the LDS performs on a read (DS_READ_B64_TR_B4): in every group of
@@ -154,11 +163,11 @@ __device__ __forceinline__ uint2 lds_read_transposed(const uint2 *row)
 }
 
 // Staging area of one wave for one chunk of 512 columns: 16 words x 32 columns x 8 bytes (the codes of a column).
-// The row of column 4 n + r of word w sits at w * 32 + ((r + rot(w)) & 3) * 8 + n (in units of 8 bytes): the
-// columns of one operand register are contiguous, and the rotation spreads the lanes of a write (eight words,
-// the same n) and of a read (four words, 128 bytes each) over the banks.
-constexpr int kStageRows = 512;
-__device__ __forceinline__ int stage_row(int w, int r, int n) { return w * 32 + (((r + w + (w >> 2)) & 3) << 3) + n; }
+// The row of column 4 n + r of word w sits at w * 40 + 8 r + n (in units of 8 bytes): the columns of one operand
+// register are contiguous; a word takes 320 bytes, so that the 64-byte pieces that the lanes of a write put into
+// adjacent words fall into different banks, and every position of a lane is a constant away from its first.
+constexpr int kStageRows = 16 * 40;
+__device__ __forceinline__ int stage_row(int w, int r, int n) { return w * 40 + 8 * r + n; }
 
 // The same operand from the two plane words (bit c = column c) of a digit row: p0 the lower plane, p1 the upper
 __device__ __forceinline__ void digit_operand_from_planes(uint32_t p0, uint32_t p1, u32x4 &dst)
@@ -202,10 +211,12 @@ __device__ __forceinline__ v8i weight_digit_operand(uint32_t hi, uint32_t lo)
     return as_operand(d);
 }
 
-__device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
+// cbsz = blgp = 4: both operands FP4 (E2M1).  `scale` is the E8M0 block scale of both operands: 127 = 2^0 for a
+// weight operand of codes 2.0 (product = digit / 2 * 2), 128 = 2^1 for a weight operand of digits (product =
+// 2 digit / 2 * 2 digit / 2 = digit * digit), so that the sums are the integers themselves.
+__device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c, int scale)
 {
-    // cbsz = blgp = 4: both operands FP4 (E2M1); block scales 2^0 (E8M0 code 127)
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, 0x7F, 0, 0x7F);
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, scale, 0, scale);
 }
 
 // NQ: chunks of 512 columns per wave; NV: activation vectors whose digit rows a wave keeps (each weight block is
@@ -217,45 +228,58 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c)
 // it measured 5-10 % slower up to 8192 columns and the same beyond: the stream starts later and a call has too few
 // units for the saved instructions to show).
 template <int NQ, int NV, int MAXS, int RU, bool PAIR>
-__global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
+__global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, const float *X0, uint32_t packed_bytes,
+                                                    uint32_t flags, int cols0, int batch, uint32_t layer_step,
+                                                    uint32_t round_step, int rounds_per_wg, int rt_count, int cq,
+                                                    int m_used, const MfmaArgs a)
 {
+    const MfmaHead h = {packed, X0, packed_bytes, flags, cols0, batch, layer_step, round_step, rounds_per_wg, rt_count, cq, m_used};
     // Units requested before the activations have arrived (a head start that keeps HBM busy during the transpose);
     // the rest of the ring follows once the digit rows are built.
 #ifndef PB_MFMA_PRE
 #define PB_MFMA_PRE 2
 #endif
     constexpr int PRE = NQ >= 4 ? (PB_MFMA_PRE < 1 ? PB_MFMA_PRE : 1) : (RU < PB_MFMA_PRE ? RU : PB_MFMA_PRE);
-    // sums per vector, bitlayer (or pair), half (digits 0-7 in units of 1, digits 8-15 in units of 2^16) and row; two buffers,
-    // used by alternate row tiles
-    __shared__ int abuf[2][NV][PB_MAX_BITS][2][kTileRows];
+    // sums per vector, bitlayer (or pair), row and quarter of the digits (even 0-6, even 8-14, odd 1-7, odd 9-15: the
+    // four operand rows of a lane of the result; the 64 lanes of a wave add to 64 different words); two buffers, used
+    // by alternate row tiles
+    __shared__ __align__(16) int abuf[2][NV][PB_MAX_BITS][kTileRows][4];
     __shared__ float s_scales[PB_MAX_BITS];
     // staging area of the activation transpose, kStageRows rows of 8 bytes per wave (none when the planes are given)
     extern __shared__ __align__(16) unsigned char stage_lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nwaves = blockDim.x >> 6;
+    const int nwaves = (h.cq + NQ - 1) / NQ;                    // = blockDim.x / 64 (the launcher's S), from a preloaded argument
     const int n0 = blockIdx.y * NV;                             // first activation vector of this workgroup
-    const int m = a.m;
+    const int m = h.m;
     const int q0 = wave * NQ;                                   // first chunk of this wave's column slice
-    const int nq = min(NQ, a.cq - q0);                          // chunks it really has (>= 1 by construction)
-    const int rt0 = blockIdx.x * a.rounds_per_wg;
-    const int rounds = min(a.rounds_per_wg, a.rt_count - rt0);  // >= 1 by construction
+    const int nq = min(NQ, h.cq - q0);                          // chunks it really has (>= 1 by construction)
+    const int rt0 = blockIdx.x * h.rounds_per_wg;
+    const int rounds = min(h.rounds_per_wg, h.rt_count - rt0);  // >= 1 by construction
     // units of a row tile: the pairs (0, 1), (2, 3), ..., and a last single bitlayer if m is odd
     const int mp = PAIR ? (m + 1) / 2 : m;
     const int U = rounds * mp;
 
-    // layer scales, lane i holds scales[i] (and the next one, for the check of the pairs): the oldest loads of
-    // the wave, so that no later wait is held up by them; parked in LDS once the digit rows are built (the
-    // barrier before the first final sum orders that store)
-    const float scv = (a.scales && lane < m) ? a.scales[lane] : 0.0f;
-    const float scn = (PAIR && a.scales && lane + 1 < m) ? a.scales[lane + 1] : 0.0f;
+    // layer scales, lane i holds scales[i] (and the next one, for the check of the pairs): requested after the
+    // first weights (nothing that a wave requests before them may depend on the argument structure, which is still
+    // on its way when a wave starts); parked in LDS once the digit rows are built (the barrier before the first final
+    // sum orders that store)
+    // (Buffer loads whose range ends after m scales, none without scales: no branch, so that the compiler's count of
+    // the loads in flight stays exact and a wait for the activations does not turn into a wait for the weights.)
+    float scv = 0.0f, scn = 0.0f;
+    auto request_scales = [&]() {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(a.scales), 0, a.scales ? m * 4 : 0, 0x00020000);
+        scv = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane * 4, 0, 0));
+        if constexpr (PAIR) scn = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, lane * 4 + 4, 0, 0));
+    };
 
     // ---- the weight stream of this wave: unit u = (round r, pair p): NQ blocks of 1 KB of the pair's low bitlayer
     // (2 p + 1, or the single one) and NQ of its high bitlayer (2 p, if the unit is a pair) ----
-    const size_t base_off = (size_t)rt0 * a.round_step + (size_t)q0 * 1024;
-    const char *base = reinterpret_cast<const char *>(a.packed) + base_off;
-    const uint32_t avail = (uint32_t)(a.packed_bytes - base_off);
+    const size_t base_off = (size_t)rt0 * h.round_step + (size_t)q0 * 1024;
+    const char *base = reinterpret_cast<const char *>(h.packed) + base_off;
+    const uint32_t avail = (uint32_t)(h.packed_bytes - base_off);
     const int voff = lane * 16;
     constexpr int SB = PAIR ? 2 * NQ : NQ;   // blocks of a unit
     u32x4 ring[RU][SB];
@@ -267,8 +291,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         // the loads in flight exactly)
         const int lo_layer = !PAIR ? ld_p : min(2 * ld_p + 1, m - 1);
         const bool has_hi = PAIR && 2 * ld_p + 1 <= m - 1;
-        const uint32_t lo_off = ld_round + (uint32_t)lo_layer * a.layer_step;
-        const uint32_t hi_off = has_hi ? lo_off - a.layer_step : lo_off;
+        const uint32_t lo_off = ld_round + (uint32_t)lo_layer * h.layer_step;
+        const uint32_t hi_off = has_hi ? lo_off - h.layer_step : lo_off;
 #pragma unroll
         for (int q = 0; q < NQ; ++q) {
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
@@ -285,14 +309,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         }
         __builtin_amdgcn_sched_barrier(0x7);
         ++ld_u;
-        if (++ld_p == mp) { ld_p = 0; ld_round += a.round_step; }
+        if (++ld_p == mp) { ld_p = 0; ld_round += h.round_step; }
     };
 
     // LDS sums start at zero.  The barrier that orders this is taken after every wave has REQUESTED its activations
     // and before any wave requests weights: the memory pipeline of a CU returns data in request order, so an
     // activation load queued behind another wave's weight loads (HBM misses) would arrive a memory latency late.
     auto zero_sums_and_meet = [&]() {
-        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * 2 * kTileRows; i += blockDim.x)
+        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * 4 * kTileRows; i += nwaves * 64)
             (&abuf[0][0][0][0][0])[i] = 0;
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -304,15 +328,15 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
     const int kb = lane >> 4;
     u32x4 pa[NV][NQ][4];
     constexpr int VG = NV > 4 ? 4 : NV;   // vectors whose activations are in flight together
-    if (a.planes) {
+    if (h.flags & kPlanesGiven) {
         const uint32_t top = (lane & 15) == 15 ? 0x22222222u : 0u;
 #pragma unroll
         for (int g = 0; g < NV; g += VG) {
             uint4 pl0[VG][NQ], pl1[VG][NQ];
 #pragma unroll
             for (int v = 0; v < VG; ++v) {
-                const int n = min(n0 + g + v, a.batch - 1);
-                const bool live = n0 + g + v < a.batch;
+                const int n = min(n0 + g + v, h.batch - 1);
+                const bool live = n0 + g + v < h.batch;
                 const uint32_t *pl =
                     a.planes + ((size_t)n * 32 + 2 * digit_of_row(lane & 15)) * (size_t)a.cwp + (size_t)q0 * 16 + 4 * kb;
 #pragma unroll
@@ -328,6 +352,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 zero_sums_and_meet();
 #pragma unroll
                 for (int k = 0; k < PRE; ++k) issue(ring[k]);
+                request_scales();
             }
 #pragma unroll
             for (int v = 0; v < VG; ++v)
@@ -353,18 +378,18 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
         // Buffer loads return 0 beyond the end of a vector (checked dword by dword), and for the vectors beyond the
         // end of the batch.
         uint2 *stage = reinterpret_cast<uint2 *>(stage_lds) + wave * kStageRows;
-        const int wr_n = lane & 7, wr_w = lane >> 3;          // a load's four columns: word 8 j + wr_w, n = wr_n
-        const int rd_e = lane & 15;
+        uint2 *const wr_row = stage + stage_row(lane >> 3, 0, lane & 7);   // a load's four columns: word 8 j + (lane >> 3), n = lane & 7
+        const uint2 *const rd_row = stage + stage_row(4 * kb, (lane >> 3) & 1, lane & 7);
         const int col0 = 512 * q0 + 4 * lane;                 // first column of the lane's load j = 0 of chunk 0
 #pragma unroll
         for (int g = 0; g < NV; g += VG) {
             u32x4 xv[VG][NQ][2];
 #pragma unroll
             for (int v = 0; v < VG; ++v) {
-                const int n = min(n0 + g + v, a.batch - 1);
-                const bool live = n0 + g + v < a.batch;
+                const int n = min(n0 + g + v, h.batch - 1);
+                const bool live = n0 + g + v < h.batch;
                 const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<float *>(a.X0 + (size_t)n * a.cols0), 0, live ? a.cols0 * 4 : 0, 0x00020000);
+                    const_cast<float *>(h.X0 + (size_t)n * h.cols0), 0, live ? h.cols0 * 4 : 0, 0x00020000);
 #pragma unroll
                 for (int q = 0; q < NQ; ++q)
 #pragma unroll
@@ -377,19 +402,19 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
             // If cols0 is a multiple of 4 a lane's four columns lie in one part and one 16-byte load serves;
             // else every column is loaded by itself.
             u32x4 xw[VG][NQ][2];
-            if (a.X1) {
+            if (h.flags & kSecondPart) {
 #pragma unroll
                 for (int v = 0; v < VG; ++v) {
-                    const int n = min(n0 + g + v, a.batch - 1);
-                    const bool live = n0 + g + v < a.batch;
+                    const int n = min(n0 + g + v, h.batch - 1);
+                    const bool live = n0 + g + v < h.batch;
                     const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
                         const_cast<float *>(a.X1 + (size_t)n * a.cols1), 0, live ? a.cols1 * 4 : 0, 0x00020000);
 #pragma unroll
                     for (int q = 0; q < NQ; ++q)
 #pragma unroll
                         for (int j = 0; j < 2; ++j) {
-                            const int c1 = col0 + 512 * q + 256 * j - a.cols0;
-                            if ((a.cols0 & 3) == 0) {
+                            const int c1 = col0 + 512 * q + 256 * j - h.cols0;
+                            if ((h.cols0 & 3) == 0) {
                                 xw[v][q][j] = __builtin_amdgcn_raw_buffer_load_b128(rx1, max(c1, 0) * 4, 0, 0);
                             } else {
 #pragma unroll
@@ -403,8 +428,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                 zero_sums_and_meet();
 #pragma unroll
                 for (int k = 0; k < PRE; ++k) issue(ring[k]);
+                request_scales();
             }
-            if (a.X1) {
+            if (h.flags & kSecondPart) {
 #pragma unroll
                 for (int v = 0; v < VG; ++v)
 #pragma unroll
@@ -413,7 +439,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         for (int j = 0; j < 2; ++j)
 #pragma unroll
                             for (int r = 0; r < 4; ++r)
-                                xv[v][q][j][r] |= col0 + 512 * q + 256 * j + r >= a.cols0 ? xw[v][q][j][r] : 0u;
+                                xv[v][q][j][r] |= col0 + 512 * q + 256 * j + r >= h.cols0 ? xw[v][q][j][r] : 0u;
             }
 #pragma unroll
             for (int v = 0; v < VG; ++v)
@@ -426,15 +452,15 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         for (int r = 0; r < 4; ++r) {
                             const uint32_t xq =
                                 (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][j][r]), a.fscale, a.imin, a.imax);
-                            stage[stage_row(8 * j + wr_w, r, wr_n)] = digit_codes(xq);
+                            wr_row[stage_row(8 * j, r, 0)] = digit_codes(xq);
                         }
                     // the wave's own writes have landed before its lanes read each other's rows
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                     __builtin_amdgcn_wave_barrier();
 #pragma unroll
                     for (int t = 0; t < 4; ++t) {
-                        const uint2 lo = lds_read_transposed(stage + stage_row(4 * kb + t, rd_e >> 3, rd_e & 7));
-                        const uint2 hi = lds_read_transposed(stage + stage_row(4 * kb + t, 2 + (rd_e >> 3), rd_e & 7));
+                        const uint2 lo = lds_read_transposed(rd_row + stage_row(t, 0, 0));
+                        const uint2 hi = lds_read_transposed(rd_row + stage_row(t, 2, 0));
                         pa[g + v][q][t] = u32x4{lo.x, lo.y, hi.x, hi.y};
                     }
                     // ... and the reads have returned before the next chunk overwrites the rows
@@ -455,15 +481,17 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
 
-    // per-lane digit weights: register c holds operand row 4 kb + c = digit d = digit_of_row(4 kb + c), which weighs
-    // 4^d; lanes kb = 0, 1 sum digits 0-7 (bits 0-15 of x_q) in units of 1, lanes kb = 2, 3 digits 8-15 (the signed
-    // upper half) in units of 2^16
-    // (the products are digit * 1 bitlayer by bitlayer and digit * digit / 4 with merged pairs)
-    float kw[4];
-#pragma unroll
-    for (int c = 0; c < 4; ++c) kw[c] = (float)(1 << (2 * (digit_of_row(4 * kb + c) & 7) + (merged ? 2 : 0)));
-
-    const int j = lane & 15, half = lane >> 5;
+    // The four registers of a lane of the result are the operand rows 4 kb + c: the digits b, b + 2, b + 4, b + 6
+    // with b = 0, 8, 1, 9 for kb = 0 .. 3.  A lane adds them up with the weights 16^c (in units of 4^b) and the sums
+    // of the four kinds of lanes stay apart until the row tile is finished.
+    // Sums of digit products are <= 9 * 2048 (a slice has at most 2048 columns): c0 + 16 c1 and c2 + 16 c3 are exact
+    // in fp32 (< 2^19), their combination is an integer below 2^27.
+    const int wscale = (PAIR && merged) ? 128 : 127;
+    auto lane_sum = [](const v4f acc) {
+        const float t0 = fmaf(acc[1], 16.0f, acc[0]), t1 = fmaf(acc[3], 16.0f, acc[2]);
+        return (int)t0 + ((int)t1 << 8);
+    };
+    const int j = lane & 15;
     // sum_c x_q[c] over the slice, as this lane's share of it in the form the sums below have (merged pairs only):
     // the product with an operand of digits 1
     int sx[NV];
@@ -477,22 +505,16 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc);
-            const float f = acc[0] * kw[0] + acc[1] * kw[1] + acc[2] * kw[2] + acc[3] * kw[3];
-            sx[v] = (int)f;
+                for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc, wscale);
+            sx[v] = lane_sum(acc);
         }
     }
     int pp = 0, pr = 0;   // pair and round of the unit being multiplied
     // the end of a pass: the sums of this lane go to `set` in LDS
     auto finish = [&](const v4f (&acc)[NV], int set, bool sign_pair) {
-        // digit weighting inside the lane.  Sums of digit products are <= 9 * 2048 in magnitude (a slice has at
-        // most 2048 columns), so c0 + 4 c1 + 16 c2 + 64 c3 < 2^21 and its multiple by 2^8 is exact in fp32, < 2^29.
 #pragma unroll
-        for (int v = 0; v < NV; ++v) {
-            const float f = acc[v][0] * kw[0] + acc[v][1] * kw[1] + acc[v][2] * kw[2] + acc[v][3] * kw[3];
-            // (the digits of the sign pair stand 2 too high in every column)
-            atomicAdd(&abuf[pr & 1][v][set][half][j], (int)f - (sign_pair ? 2 * sx[v] : 0));
-        }
+        for (int v = 0; v < NV; ++v)   // (the digits of the sign pair stand 2 too high in every column)
+            atomicAdd(&abuf[pr & 1][v][set][j][kb], lane_sum(acc[v]) - (sign_pair ? 2 * sx[v] : 0));
     };
     for (int u0 = 0; u0 < U; u0 += RU) {
 #pragma unroll
@@ -514,7 +536,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         for (int t = 0; t < 4; ++t) {
                             const v8i b = weight_digit_operand(wh[t], wl[t]);
 #pragma unroll
-                            for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
+                            for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v], wscale);
                         }
                     }
                     finish(acc, pp, sign_pair);
@@ -532,7 +554,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                             for (int t = 0; t < 4; ++t) {
                                 const v8i b = weight_operand(w[t]);
 #pragma unroll
-                                for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v]);
+                                for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v], wscale);
                             }
                         }
                         finish(acc, lo_layer - h, false);
@@ -555,26 +577,24 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const MfmaArgs a)
                         const int v = slot / LG, lg = slot % LG, jrow = lane & 15, n = n0 + v;
                         const int prow = (rt0 + pr) * kTileRows + jrow;
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
-                        const bool live = v < NV && n < a.batch && row >= 0 && row < a.R;
-                        int *src = &abuf[pr & 1][v < NV ? v : 0][lg][0][jrow];
+                        const bool live = v < NV && n < h.batch && row >= 0 && row < a.R;
+                        int4 *src = reinterpret_cast<int4 *>(&abuf[pr & 1][v < NV ? v : 0][lg][jrow][0]);
                         double z = 0.0;
                         if (v < NV) {
-                            for (int i = lg; i < nsets; i += LG, src += LG * 2 * kTileRows) {
-                                const int r_lo = src[0], s_hi = src[kTileRows];
-                                src[0] = 0;
-                                src[kTileRows] = 0;
-                                // the sum is lo + hi * 2^16 exactly: 0 <= lo < 2^32 (unsigned) and |hi| < 2^31, except
-                                // that the low half of the sign pair lies in [-2^31, 2^30] (signed)
-                                const long long s_lo =
-                                    (merged && i == 0 && m >= 2) ? (long long)r_lo : (long long)(uint32_t)r_lo;
+                            for (int i = lg; i < nsets; i += LG, src += LG * kTileRows) {
+                                // the quarters: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in units of 4^8, digits
+                                // 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below 2^31 in magnitude
+                                // (4369 * 9 * 32768 columns)
+                                const int4 q = *src;
+                                *src = make_int4(0, 0, 0, 0);
+                                const long long sum = (long long)q.x + 4 * (long long)q.z +
+                                                      (((long long)q.y + 4 * (long long)q.w) << 16);
                                 if (a.A) {
-                                    if (live)
-                                        a.A[((size_t)i * a.batch + n) * (size_t)a.R + row] =
-                                            s_lo + ((long long)s_hi << 16);
+                                    if (live) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
                                 } else {
                                     // a merged pair carries the scale of its low bitlayer
                                     const int si = !merged ? i : min(2 * i + 1, m - 1);
-                                    z = fma((double)s_scales[si], fma((double)s_hi, 65536.0, (double)s_lo), z);
+                                    z = fma((double)s_scales[si], (double)sum, z);
                                 }
                             }
                         }
@@ -708,17 +728,19 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
                 int batch, float *Y, long long *A, bool pairs_out, const Epilogue &ep, hipStream_t st)
 {
     MfmaArgs a;
-    a.packed = packed; a.X0 = X0; a.X1 = X1; a.planes = planes; a.scales = scales; a.Y = Y; a.A = A;
+    MfmaHead h;
+    h.packed = packed; h.X0 = X0; a.X1 = X1; a.planes = planes; a.scales = scales; a.Y = Y; a.A = A;
     a.pairs_out = (A && pairs_out) ? 1 : 0;
     a.bias = ep.bias; a.relu = ep.relu; a.c_prev = ep.c_prev; a.h_out = ep.h_out; a.c_out = ep.c_out;
     a.gate_h = L.gate_h;
-    a.packed_bytes = packed_bytes(L);
-    a.layer_step = (uint32_t)(tile16_layer_stride(L) * 4);
-    a.round_step = (uint32_t)(tile16_rowtile_stride(L) * 4);
-    a.cols0 = cols0; a.cols1 = cols1;
-    a.R = L.rows; a.rt_count = L.rt_count; a.cq = L.cq; a.cwp = L.cwp;
-    a.m = bits_used;
-    a.batch = batch;
+    h.packed_bytes = (uint32_t)packed_bytes(L);   // (the host API refuses matrices of 4 GiB and more)
+    h.flags = (planes ? kPlanesGiven : 0u) | (X1 ? kSecondPart : 0u);
+    h.layer_step = (uint32_t)(tile16_layer_stride(L) * 4);
+    h.round_step = (uint32_t)(tile16_rowtile_stride(L) * 4);
+    h.cols0 = cols0; a.cols1 = cols1;
+    a.R = L.rows; h.rt_count = L.rt_count; h.cq = L.cq; a.cwp = L.cwp;
+    h.m = bits_used;
+    h.batch = batch;
     a.fscale = ldexpf(1.0f, frac_bits);
     a.imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
     a.imin = -a.imax - 1;
@@ -743,10 +765,11 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     int wgs = capacity / groups;
     if (wgs < 1) wgs = 1;
     if (wgs > L.rt_count) wgs = L.rt_count;
-    a.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
-    wgs = (L.rt_count + a.rounds_per_wg - 1) / a.rounds_per_wg;
-    void *args[] = {&a};
-    const Variant &run = kVariants[pick_ring(vi, a.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used))];
+    h.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
+    wgs = (L.rt_count + h.rounds_per_wg - 1) / h.rounds_per_wg;
+    void *args[] = {&h.packed, &h.X0, &h.packed_bytes, &h.flags, &h.cols0, &h.batch, &h.layer_step, &h.round_step,
+                    &h.rounds_per_wg, &h.rt_count, &h.cq, &h.m, &a};
+    const Variant &run = kVariants[pick_ring(vi, h.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used))];
     const hipError_t e = hipLaunchKernel(pair ? run.fn_pair : run.fn, dim3((unsigned)wgs, (unsigned)groups),
                                          dim3((unsigned)S * 64), args, planes ? 0 : stage_bytes(S), st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
