@@ -80,9 +80,9 @@ typedef struct pb_desc {
 } pb_desc;
 
 /* Fill *d (host) for a rows x cols matrix with `bits` bitlayers and the
- * defaults f = 16, k = 32.  pb_desc_init picks the layout of the fastest kernel
- * for the shape (PB_LAYOUT_TILE16_V1 up to 16384 columns, else
- * PB_LAYOUT_ROWMAJOR_V1); pb_desc_init_layout takes it from the caller.
+ * defaults f = 16, k = 32.  pb_desc_init picks PB_LAYOUT_TILE16_V1 (the layout
+ * of the matrix-core kernel, the fastest for every shape the interface
+ * allows); pb_desc_init_layout takes the layout from the caller.
  * PB_EINVAL / PB_ESIZE on bad shapes or a layout that does not fit the shape. */
 int pb_desc_init(pb_desc *d, int rows, int cols, int bits);
 int pb_desc_init_layout(pb_desc *d, int rows, int cols, int bits, uint32_t layout);
@@ -174,8 +174,7 @@ int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const flo
  * bits_used is 1), P[p] = 2 A_(2p) + A_(2p+1), P[last] = A_(bits_used-1) for a
  * single one.
  * A: [(bits_used + 1) / 2][batch][rows] int64, written.  Tiled layouts only
- * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1) and cols <= 16384 (PB_ESIZE beyond: wider
- * matrices are multiplied bitlayer by bitlayer, the pair sums would not fit).  pb_matmul with more than one vector
+ * (PB_EINVAL for PB_LAYOUT_ROWMAJOR_V1).  pb_matmul with more than one vector
  * takes this route by itself when scales[0] == -2 * scales[1] and scales[2p] ==
  * 2 * scales[2p + 1] hold for every pair, else it multiplies bitlayer by
  * bitlayer. */
@@ -198,10 +197,18 @@ int pb_calib_mfma(int mode, int iters, int workgroups, float *out, void *stream)
  * to the same activations (or that time the halves separately):
  * pb_act_prep converts X to fixed point and writes its bit planes and plane
  * statistics into `workspace` (Algorithm 2, x_q = Int(x * 2^f), and the bitwise
- * transpose of Section 3.4); pb_matmul_prepared runs the AND + popcount product
- * and the scale-accumulation on planes left there by pb_act_prep for a
- * descriptor with the same cols, frac_bits and act_bits and the same batch.
- * pb_matmul(...) == pb_act_prep(...) followed by pb_matmul_prepared(...). */
+ * transpose of Section 3.4); pb_matmul_prepared runs the product (AND +
+ * popcount on PB_LAYOUT_ROWMAJOR_V1, the matrix-core kernel on the tiled
+ * layouts, which then builds its operands from the planes) and the
+ * scale-accumulation on planes left there by pb_act_prep.
+ * The planes are laid out for the descriptor they were made with: the
+ * descriptor of pb_matmul_prepared must have the same cols, LAYOUT, frac_bits
+ * and act_bits, and the call the same batch (the distance between two planes
+ * is the padded row length of the layout; another layout would read other
+ * words, and nothing can check this).  Matrices that differ in rows and bits
+ * only may share one pb_act_prep.
+ * pb_matmul(...) computes the same Y as pb_act_prep(...) followed by
+ * pb_matmul_prepared(...). */
 int pb_act_prep(const pb_desc *d, const float *X, int batch, void *workspace, void *stream);
 int pb_matmul_prepared(const void *packed, const float *scales, const pb_desc *d, int bits_used, int batch, float *Y,
                        void *workspace, void *stream);

@@ -24,7 +24,6 @@
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include "pb.h"
 
@@ -40,7 +39,9 @@ constexpr int kTileRows = 16;       // matrix-core kernel: rows per tile
 constexpr int kChunkWords = 16;     // matrix-core kernel: words per row in one block
 constexpr int kMaxSlices = 16;      // matrix-core kernel: waves (column slices) per workgroup
 constexpr int kMaxColsTile16 = 32768;     // 16 slices of 2048 columns
-constexpr int kMaxColsPairs = 16384;      // merged bitlayer pairs: their sums of digit products up to 9 fit 32 bits
+// merged bitlayer pairs (digit products up to 9): a quarter sum stays below 4369 * 9 * 32768 < 2^31, so pairs cover
+// every width the tiled layouts have
+constexpr int kMaxColsPairs = 32768;
 
 struct Layout {
     uint32_t layout;
@@ -84,10 +85,8 @@ inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L
     if (layout == PB_LAYOUT_ROWMAJOR_V1) {
         int best_ws = 0, best_pad = 0;
         const int cand[3] = {128, 64, 32};
-        const char *force = getenv("PB_TUNE_WS");
         for (int k = 0; k < 3; ++k) {
             int ws = cand[k];
-            if (force && atoi(force) != ws) continue;
             int cs = (L->cw + ws - 1) / ws;
             if (cs > kMaxWavesPerWG) continue;
             int pad = cs * ws;

@@ -356,9 +356,6 @@ int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, 
     a.rpt_shift = ilog2(L.rpt);
     a.csplit_magic = 65536 / L.csplit + 1;   // (wave * magic) >> 16 == wave / csplit for wave < 8
     a.rwaves = L.csplit == 1 ? 4 : (L.csplit <= 4 ? 2 : 1);
-    int target_wgs = 512;
-    if (const char *e = getenv("PB_TUNE_RWAVES")) a.rwaves = atoi(e);
-    if (const char *e = getenv("PB_TUNE_WGS")) target_wgs = atoi(e);
     if (a.csplit * a.rwaves > kMaxWavesPerWG) a.rwaves = 1;
     a.m = bits_used;
     a.num_rowgroups = L.rows_p / L.rpt;
@@ -366,11 +363,9 @@ int launch_matvec(const uint32_t *packed, const float *scales, const Layout &L, 
     a.out_scale = ldexp(1.0, -frac_bits);
     // Waves: one per SIMD (1024) while a wave then has at most 8 tiles, else two per SIMD; every wave repeats the
     // plane fetch and the epilogue, so more waves only pay off once each has enough tiles to overlap with.
-    if (!getenv("PB_TUNE_WGS")) {
-        const long long tiles_per_wave_at_1024 = (long long)a.num_rowgroups * bits_used * a.csplit / 1024;
-        const int waves_total = tiles_per_wave_at_1024 <= 8 ? 1024 : 2048;
-        target_wgs = waves_total / (a.csplit * a.rwaves);
-    }
+    const long long tiles_per_wave_at_1024 = (long long)a.num_rowgroups * bits_used * a.csplit / 1024;
+    const int waves_total = tiles_per_wave_at_1024 <= 8 ? 1024 : 2048;
+    int target_wgs = waves_total / (a.csplit * a.rwaves);
     if (target_wgs < 1) target_wgs = 1;
     long long per_wg = ((long long)a.num_rowgroups + target_wgs - 1) / target_wgs;
     int gw = (int)((per_wg + a.rwaves - 1) / a.rwaves);

@@ -236,10 +236,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const MfmaHead h = {packed, X0, packed_bytes, flags, cols0, batch, layer_step, round_step, rounds_per_wg, rt_count, cq, m_used};
     // Units requested before the activations have arrived (a head start that keeps HBM busy during the transpose);
     // the rest of the ring follows once the digit rows are built.
-#ifndef PB_MFMA_PRE
-#define PB_MFMA_PRE 2
-#endif
-    constexpr int PRE = NQ >= 4 ? (PB_MFMA_PRE < 1 ? PB_MFMA_PRE : 1) : (RU < PB_MFMA_PRE ? RU : PB_MFMA_PRE);
+    // (two units measured best: with three or four a call of 4096 or 8192 columns takes 0.2-0.5 us longer)
+    constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
     // sums per vector, bitlayer (or pair), row and quarter of the digits (even 0-6, even 8-14, odd 1-7, odd 9-15: the
     // four operand rows of a lane of the result; the 64 lanes of a wave add to 64 different words); two buffers, used
     // by alternate row tiles
@@ -653,15 +651,23 @@ static const Variant kVariants[] = {
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-// Tuning overrides from the environment (for sweeps over the variants), read once: 0 / -1 = not set.
+// Overrides of the launcher's choices (chunks and vectors per wave, ring depth, workgroups, pairs), for sweeps over
+// the variants: compiled in only with -DPB_TUNING (a tuning build reads them from the environment once); the
+// product build has none and its behaviour does not depend on the environment.  0 / -1 = not set.
 struct Tuning {
-    int nq, nv, ru, wgs, pair;
+    int nq = 0, nv = 0, ru = 0, wgs = 0, pair = -1;
+#ifdef PB_TUNING
     Tuning()
     {
         auto get = [](const char *name, int unset) { const char *e = getenv(name); return e ? atoi(e) : unset; };
         nq = get("PB_TUNE_NQ", 0); nv = get("PB_TUNE_NV", 0); ru = get("PB_TUNE_RU", 0);
         wgs = get("PB_TUNE_WGS", 0); pair = get("PB_TUNE_PAIR", -1);
+        if (nq < 0) nq = 0;
+        if (nv < 0) nv = 0;
+        if (ru < 0) ru = 0;
+        if (wgs < 0) wgs = 0;
     }
+#endif
 };
 static const Tuning &tuning()
 {
@@ -715,8 +721,21 @@ static int resident_workgroups(int variant, int S, bool pair)
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    // (a workgroup's dynamic LDS may exceed the default limit of 64 KB, a compute unit of this chip has 160 KB:
+    // declared for this variant and its siblings of other ring depths, one of which is the one launched)
+    const void *fn = pair ? kVariants[variant].fn_pair : kVariants[variant].fn;
+    if (stage_bytes(S) > 32 * 1024) {
+        for (int i = 0; i < kNumVariants; ++i) {
+            const Variant &o = kVariants[i];
+            if (o.nq != kVariants[variant].nq || o.nv != kVariants[variant].nv || o.maxs != kVariants[variant].maxs)
+                continue;
+            if (hipFuncSetAttribute(pair ? o.fn_pair : o.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)stage_bytes(S)) != hipSuccess)
+                return 0;
+        }
+    }
     if (hipOccupancyMaxActiveBlocksPerMultiprocessor(
-            &per_cu, pair ? kVariants[variant].fn_pair : kVariants[variant].fn, S * 64, stage_bytes(S)) != hipSuccess)
+            &per_cu, fn, S * 64, stage_bytes(S)) != hipSuccess)
         return 0;
     v = cus * per_cu;
     if (v > 0) __atomic_store_n(slot, v, __ATOMIC_RELAXED);

@@ -52,7 +52,7 @@ def run_layer(pb, W, bits, X, m_list, frac_bits=16, act_bits=32, check_y=True, l
         bad = A_gpu != ref["A"]
         assert not bad.any(), "int64 accumulators differ at %s (R=%d C=%d bits=%d m=%d)" % (
             np.argwhere(bad)[:5].tolist(), R, C, bits, m)
-        if lin.desc.layout != LAYOUTS["popc"] and C <= 16384:
+        if lin.desc.layout != LAYOUTS["popc"]:
             # the sums of the bitlayer pairs, as the matrix-core kernel holds them on its usual route
             P_gpu = lin.acc_pairs(Xd, m).cpu().numpy()
             bad = P_gpu != pair_sums(ref["A"], m)
@@ -186,6 +186,92 @@ def test_special_activation_vectors(pb, layout):
         run_layer(pb, W, bits, X, [1, 3, 5], layout=layout)
 
 
+def test_non_finite_and_signed_zero_activations(pb, layout):
+    """NaN converts to 0, +-inf saturate, -0.0 is 0 (Algorithm 2's Int(x * 2^16) as the interface defines it for
+    values a cast does not cover), through the conversion inside the product kernels: batch 1, batches that
+    fill and that do not fill a vector group, a vector of nothing but NaN, one of -inf."""
+    R, C, bits = 45, 1300, 5
+    W, X = synth.ragged(R, C, batch=9, case=41, xdist="normal")
+    X = X.copy()
+    rng = np.random.default_rng(200300822 + 41)
+    idx = rng.choice(X.size, size=X.size // 6, replace=False)
+    X.flat[idx] = rng.choice(np.array([np.nan, np.inf, -np.inf, -0.0, 0.0, 3.0e38, -3.0e38, 1e-40, -1e-40],
+                                      dtype=np.float32), size=idx.size)
+    X[3, :] = np.nan
+    X[4, :] = -np.inf
+    X[:, 517] = np.inf          # a whole column
+    X[:, 1299] = np.nan         # the last one
+    for N in (1, 2, 5, 9):
+        print("non-finite, batch", N, flush=True)
+        run_layer(pb, W, bits, X[:N], [1, 4, 5], layout=layout)
+    # narrower activations: +-inf saturate at the k-bit range
+    run_layer(pb, W, bits, X[:5], [5], frac_bits=4, act_bits=8, layout=layout)
+
+
+def test_non_finite_activations_in_a_concatenated_input(pb):
+    """The LSTM wrapper's [x_t ; h] input: both parts go through the same conversion."""
+    H, I, bits, N = 37, 100, 4, 3
+    g = np.random.default_rng(200300822 + 43)
+    W = g.uniform(-0.04, 0.04, size=(4 * H, I + H)).astype(np.float32)
+    x = g.normal(size=(N, I)).astype(np.float32)
+    h = g.uniform(-1, 1, size=(N, H)).astype(np.float32)
+    c = g.uniform(-1, 1, size=(N, H)).astype(np.float32)
+    x[0, 5] = np.nan; x[1, 99] = np.inf; h[2, 0] = -np.inf; h[0, 36] = np.nan; x[2, 0] = -0.0
+    for lay in (GATES, LAYOUTS["mfma"]):
+        lin = pb.PackedLinear(dev(W), bits, max_batch=N, layout=lay)
+        prep = po.prepare(W, bits)
+        lw = po.pack_words(prep["layers"])
+        xh = np.concatenate([x, h], axis=1)
+        _, Y = po.matmul_words(lw, prep["scales"], bits, I + H, xh)
+        h_ref, c_ref = po.lstm_pointwise(Y, None, c)
+        h_out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        c_out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        pb.pb_lstm_cell(lin.packed, lin.scales, lin.desc, bits, dev(x), I, dev(h), dev(c), None, h_out, c_out, N,
+                        lin.workspace)
+        assert np.abs(h_out.cpu().numpy() - h_ref).max() <= 2e-6
+        assert np.abs(c_out.cpu().numpy() - c_ref).max() <= 2e-6
+
+
+def limit_matrices(cols, bits):
+    """Weight codes that put every partial sum of the kernels at its bound: all -1 (every bitlayer all ones; a row
+    of its own holds +qmax, which fixes the step at 1) and all +qmax (sign bitlayer empty, all others full: the
+    largest digit of every bitlayer pair, the sign pair included)."""
+    qmax = 2 ** (bits - 1) - 1
+    Wa = -np.ones((18, cols), dtype=np.float32)
+    Wa[17, :] = 0.0
+    Wa[17, 0] = float(qmax)
+    Wb = np.full((17, cols), float(qmax), dtype=np.float32)
+    return [("all ones", Wa), ("all qmax", Wb)]
+
+
+def limit_vectors(cols):
+    """Saturated activations: x_q = INT32_MAX, INT32_MIN, 0xFFFF, -1, alternating extremes."""
+    X = np.empty((5, cols), dtype=np.float32)
+    X[0] = 40000.0
+    X[1] = -40000.0
+    X[2] = 65535.0 / 65536.0
+    X[3] = -1.0 / 65536.0
+    X[4] = np.where(np.arange(cols) % 2 == 0, 40000.0, -40000.0)
+    return X
+
+
+@pytest.mark.parametrize("cols", [32768, 16384, 32768 - 31])
+def test_partial_sums_at_their_limits(pb, layout, cols):
+    """The widest matrices times saturated activations: the 32-bit pieces in which the kernels hold the exact sums of
+    Algorithm 2 are as large as they get (tests/test_accumulator_bounds.py works the bounds out on the host).
+    Single bitlayers, bitlayer pairs (sign pair included), batch 1 and a batch."""
+    bits = 8
+    X = limit_vectors(cols)
+    for name, W in limit_matrices(cols, bits):
+        prep = po.prepare(W, bits)
+        assert prep["d"] == 1.0 and int(prep["q"].min()) in (-1, 2 ** (bits - 1) - 1)
+        print("limits", cols, name, "batch 5", flush=True)
+        run_layer(pb, W, bits, X, [1, 2, 7, 8], layout=layout)
+        for n in range(5):
+            print("limits", cols, name, "vector", n, flush=True)
+            run_layer(pb, W, bits, X[n:n + 1], [2, 8], layout=layout)
+
+
 def test_reduced_activation_precision(pb, layout):
     # Section 3.1: k (activation precision) of 8 or 16 planes; the fixed point moves with it
     W, X = synth.ragged(50, 300, batch=2, case=5, xdist="uniform")
@@ -212,8 +298,8 @@ def test_prepared_halves_equal_whole_call(pb, layout, fmt):
 
 
 @pytest.mark.parametrize("fk", [(6, 8), (10, 16), (14, 16)])
-def test_sixteen_plane_variant_with_batch_and_saturation(pb, fk):
-    """act_bits <= 16 runs the 16-plane variant of the matrix-core kernel; wide inputs saturate at k bits."""
+def test_narrow_activations_with_batch_and_saturation(pb, fk):
+    """act_bits <= 16 (Section 3.1: fewer activation bits) on the matrix-core kernel; wide inputs saturate at k bits."""
     f, k = fk
     W, X = synth.ragged(90, 1300, batch=5, case=23, xdist="wide")
     run_layer(pb, W, 6, X, [1, 4, 6], frac_bits=f, act_bits=k, layout=LAYOUTS["mfma"])
