@@ -378,38 +378,113 @@ def test_sign_quantizer_hand_values_and_mean():
     assert err(float(d)) <= min(err(float(d) * 1.01), err(float(d) * 0.99))
 
 
-def _clip_search_brute_force(W, bits):
-    """The clipping search spelled out with numpy fp32 scalars and Python integers."""
+def test_clip_search_worked_by_hand():
+    """Section 3.3's clipping search on a case small enough to do on paper.  W = [32, 6, -6, 6, -6, 5, -5], B = 2:
+    codes -2 .. 1, thresholds T_k = 32 k / 32 = k, step d_k = T_k / 1 = k, error = sum |W - d q| (mean x 7).
+    The 32 always gets code 1 (error 32 - k); for the six small weights:
+      k = 6: 6 -> 1, -6 -> -1 (0 each); 5 -> 1, -5 -> -1 (1 each)                    26 + 0 + 2 = 28   <- smallest
+      k = 5: +-6 -> +-1 (1 each, four of them); +-5 -> +-1 (0)                       27 + 4 + 0 = 31   runner-up
+      k = 7: +-6 -> +-1 (1 each); +-5 -> +-1 (2 each)                                25 + 4 + 4 = 33
+      k = 4: 6 / 4 = 1.5 -> 2 (half to even), clamped to 1 (2 each); -6 -> -2 (2 each); +-5 -> +-1 (1 each)
+                                                                                    28 + 8 + 2 = 38
+      k = 3: 6 -> 2 -> clamped 1 (3 each); -6 -> -2 (0); 5 -> 2 -> 1 (2); -5 -> -2 (1)   29 + 6 + 3 = 38
+      k >= 12: all six round to 0                                                   (32 - k) + 34, 34 at k = 32
+    so clipping at T = 6 wins with step 6 and codes [1, 1, -1, 1, -1, 1, -1].
+    With squared errors the unclipped k = 32 would win (194 against 678 at k = 6): the measure is the absolute error."""
+    W = np.array([32, 6, -6, 6, -6, 5, -5], dtype=np.float32)
+    q, d = po.quantize_mode(W, 2, po.QUANT_CLIP)
+    assert d == 6.0 and q.tolist() == [1, 1, -1, 1, -1, 1, -1]
+    # the same weights scaled by 2^-7 (all values stay exact): the step scales, the codes stay
+    q, d = po.quantize_mode(W * np.float32(2.0 ** -7), 2, po.QUANT_CLIP)
+    assert d == 6.0 * 2.0 ** -7 and q.tolist() == [1, 1, -1, 1, -1, 1, -1]
+
+
+def test_clip_search_tie_takes_the_larger_threshold():
+    """W = [32, -10, 2, 9, 4, -9], B = 2 (step d_k = k):
+      k = 10: 22 + |-10 + 10| + 2 + |9 - 10| + 4 + |-9 + 10| = 22 + 0 + 2 + 1 + 4 + 1 = 30
+      k =  9: 23 + |-10 +  9| + 2 + |9 -  9| + 4 + |-9 +  9| = 23 + 1 + 2 + 0 + 4 + 0 = 30
+      k = 11: 21 + 1 + 2 + 2 + 4 + 2 = 32, every other k is larger still (34 at k = 32).
+    Two thresholds tie exactly; the reading keeps the larger one (the one that clips less)."""
+    W = np.array([32, -10, 2, 9, 4, -9], dtype=np.float32)
+    q, d = po.quantize_mode(W, 2, po.QUANT_CLIP)
+    assert d == 10.0 and q.tolist() == [1, -1, 0, 1, 0, -1]
+
+
+def _exact_clip_errors(W, bits):
+    """sum |W - d_k q| for k = 1 .. 32 in exact rational arithmetic; d_k is the fp32 step of threshold max|W| k / 32,
+    q = round-half-even(W / d_k) clamped to the B-bit codes."""
+    from fractions import Fraction as Fr
     f32 = np.float32
     M = f32(np.abs(W).max())
-    e = int(np.floor(np.log2(float(M))))
     qmax, qmin = (1 << (bits - 1)) - 1, -(1 << (bits - 1))
-    qm = f32(max(qmax, 1))
-    best = None
-    for k in range(32, 0, -1):
-        d = f32(f32(M * f32(f32(k) * f32(0.03125))) / qm)
-        q = np.clip(np.rint((W / d).astype(np.float32)), qmin, qmax).astype(np.int32)
-        resid = np.abs((W - (d * q.astype(np.float32)).astype(np.float32)).astype(np.float32))
-        E = sum(int(np.trunc(np.ldexp(np.float64(v), 30 - e))) for v in resid)
-        if best is None or E < best[0]:
-            best = (E, k, d, q)
-    return best
+    out = {}
+    for k in range(1, 33):
+        d32 = f32(f32(M * f32(k / 32.0)) / f32(max(qmax, 1)))
+        d = Fr(float(d32))
+        E = Fr(0)
+        for w in W:
+            w = Fr(float(w))
+            t = w / d
+            fl = t.numerator // t.denominator
+            r = t - fl
+            qq = fl + 1 if r > Fr(1, 2) else fl if r < Fr(1, 2) else (fl if fl % 2 == 0 else fl + 1)
+            # (the oracle rounds the fp32 quotient; a quotient within half an ulp of a tie may round the other way,
+            # which changes |W - d q| by at most 2^-23 |W|: inside the slack of the caller)
+            qq = min(max(qq, qmin), qmax)
+            E += abs(w - d * qq)
+        out[k] = (E, d32)
+    return out
 
 
-@pytest.mark.parametrize("bits", [1, 2, 3, 4, 8])
-def test_clip_search_against_brute_force(bits):
-    rng = np.random.default_rng(40 + bits)
-    W = rng.normal(0, 0.05, size=400).astype(np.float32)
-    W[7] = 1.0                                                   # an outlier: clipping pays off
-    E, k, d_ref, q_ref = _clip_search_brute_force(W, bits)
+@pytest.mark.parametrize("bits,seed", [(2, 1), (3, 2), (4, 3), (5, 4), (8, 5)])
+def test_clip_search_minimises_the_exact_mean_absolute_error(bits, seed):
+    """The winner's exact error is the smallest of the 32 candidates' exact errors, up to what the oracle's own
+    arithmetic loses: fp32 rounding of each product and difference (2^-23 of max|W| per element, twice) and the
+    truncation of each term to a multiple of 2^(e-30)."""
+    from fractions import Fraction as Fr
+    rng = np.random.default_rng(400 + seed)
+    W = rng.normal(0, 0.05, size=300).astype(np.float32)
+    W[11] = 0.9                                                  # an outlier: clipping pays off
     q, d = po.quantize_mode(W, bits, po.QUANT_CLIP)
-    assert d == d_ref and (q == q_ref).all()
-    if bits >= 3:
-        assert k < 32
-        # and the true mean error is no larger than without clipping
-        q0, d0 = po.quantize(W, bits)
-        mae = lambda qq, dd: np.abs(W.astype(np.float64) - float(dd) * qq).mean()
+    errs = _exact_clip_errors(W, bits)
+    mine = [k for k, (E, d32) in errs.items() if d32 == d]
+    assert mine, "the step is not one of the 32 candidates"
+    k_star = max(mine)
+    slack = Fr(len(W)) * Fr(float(np.abs(W).max())) * Fr(3, 2 ** 23)
+    best = min(E for E, _ in errs.values())
+    assert errs[k_star][0] <= best + slack
+    if 3 <= bits <= 5:
+        assert k_star < 32                                        # the outlier is clipped (a coarse grid gains from it)
+    # codes are those of the symmetric quantizer with that step
+    qmax, qmin = (1 << (bits - 1)) - 1, -(1 << (bits - 1))
+    q_ref = np.clip(np.rint((W / d).astype(np.float32)), qmin, qmax).astype(np.int32)
+    assert (q == q_ref).all()
+    # a different objective or candidate set would not pass: the squared-error optimum and the unclipped step differ
+    q0, d0 = po.quantize(W, bits)
+    mae = lambda qq, dd: np.abs(W.astype(np.float64) - float(dd) * qq).mean()
+    if 3 <= bits <= 5:
+        assert mae(q, d) < mae(q0, d0)
+    else:
         assert mae(q, d) <= mae(q0, d0)
+
+
+def test_clip_search_invariances():
+    """Order of the weights does not matter (the error sums are exact integers); scaling by 2^p scales the step by 2^p
+    and leaves the codes."""
+    rng = np.random.default_rng(77)
+    W = rng.normal(0, 0.05, size=500).astype(np.float32)
+    W[3] = -1.25
+    for bits in (2, 4, 7):
+        q, d = po.quantize_mode(W, bits, po.QUANT_CLIP)
+        perm = rng.permutation(W.size)
+        qp, dp = po.quantize_mode(W[perm], bits, po.QUANT_CLIP)
+        assert dp == d and (qp == q[perm]).all()
+        for p in (-9, 5):
+            qs, ds = po.quantize_mode((W * np.float32(2.0 ** p)).astype(np.float32), bits, po.QUANT_CLIP)
+            assert ds == np.float32(d * np.float32(2.0 ** p)) and (qs == q).all()
+        # the mirror image: the code range is not symmetric (-2^(B-1) .. 2^(B-1) - 1), the threshold search is
+        qn, dn = po.quantize_mode(-W, bits, po.QUANT_CLIP)
+        assert np.abs(W.astype(np.float64) + float(dn) * qn).mean() <= np.abs(W.astype(np.float64)).mean()
 
 
 def test_clip_search_keeps_an_exact_grid():
