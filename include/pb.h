@@ -151,6 +151,22 @@ int pb_unpack(const void *packed, const pb_desc *d, int32_t *q, void *stream);
 int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X, int batch,
               float *Y, void *workspace, void *stream);
 
+/* pb_matmul for callers that cannot allocate device memory (code under HIP
+ * graph capture, serving loops that own no buffers, harnesses that forbid
+ * hipMalloc): the same kernels and the same result as pb_matmul, with the
+ * workspace (bit planes and plane statistics of the activations, which only the
+ * PB_LAYOUT_ROWMAJOR_V1 kernels use) in a device array of
+ * PB_STATIC_SCRATCH_BYTES that the library holds on every GPU it runs on until
+ * the process ends.  Allocates, frees and synchronises nothing.
+ * PB_ESIZE if pb_workspace_bytes(d, batch) exceeds PB_STATIC_SCRATCH_BYTES
+ * (a 4096 x 4096 matrix: up to 63 vectors; 32768 columns: up to 14).
+ * All calls on one GPU share that array: calls that may overlap in time on one
+ * GPU (different streams, different threads) race on it and must be serialised by
+ * the caller; use pb_matmul with separate workspaces for concurrent calls. */
+#define PB_STATIC_SCRATCH_BYTES (2u << 20)
+int pb_matmul_static(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X, int batch,
+                     float *Y, void *stream);
+
 /* pb_matmul with the layer's bias and nonlinearity applied before the store (the paper replaces each linear
  * layer and keeps the nonlinearities in fp32, Sections 4.2-4.3):
  *   Y[n][r] = act( fp32(sum_i scales[i] * A_i[r] * 2^-f) + bias[r] ),  act = identity or max(., 0).

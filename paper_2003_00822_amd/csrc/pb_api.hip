@@ -27,6 +27,32 @@ int check_desc(const pb_desc *d, pb::Layout *L)
     return PB_OK;
 }
 
+// Scratch memory of the entry point that allocates nothing (pb_matmul_static): the workspace of a pb_matmul call,
+// held by the library in a static device array.  Every GPU the library runs on has its own copy; the array's name
+// is a host-side stand-in, the device address comes from hipGetSymbolAddress, once per device.
+constexpr size_t kScratchBytes = PB_STATIC_SCRATCH_BYTES;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on device i, null until its first use there
+
+// Device address of `scratch` on the current device (looked up on first use, with that device current).
+int scratch_address(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return (int)e;
+    if (dev < 0 || dev >= kMaxDevices) return (int)hipErrorInvalidDevice;
+    void *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return (int)e;
+        if (!p) return (int)hipErrorInvalidSymbol;
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return 0;
+}
+
 int hip_status(int err)
 {
     if (err == 0) return PB_OK;
@@ -146,6 +172,22 @@ int pb_matmul(const void *packed, const float *scales, const pb_desc *d, int bit
 {
     if (!Y || !d) return PB_EINVAL;
     return matmul_common(packed, scales, d, bits_used, X, d->cols, nullptr, 0, batch, Y, nullptr, workspace, stream);
+}
+
+int pb_matmul_static(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X, int batch,
+                     float *Y, void *stream)
+{
+    if (!Y || !d) return PB_EINVAL;
+    pb::Layout L;
+    int rc = check_desc(d, &L);
+    if (rc != PB_OK) return rc;
+    if (batch < 1) return PB_EINVAL;
+    if (batch > PB_MAX_BATCH || pb::workspace_bytes(L, batch) > kScratchBytes) return PB_ESIZE;
+    void *ws = nullptr;
+    rc = scratch_address(&ws);
+    if (rc) return hip_status(rc);
+    // (nothing in the scratch has to start at zero: the activation kernel writes every word the product kernel reads)
+    return matmul_common(packed, scales, d, bits_used, X, d->cols, nullptr, 0, batch, Y, nullptr, ws, stream);
 }
 
 int pb_matmul_bias_act(const void *packed, const float *scales, const pb_desc *d, int bits_used, const float *X,

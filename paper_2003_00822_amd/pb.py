@@ -27,7 +27,7 @@ PB_QUANT_SYMMETRIC, PB_QUANT_RANGE, PB_QUANT_SIGN, PB_QUANT_CLIP_SEARCH = 0, 1, 
 
 EXPORTS = [
     "pb_desc_init", "pb_desc_init_layout", "pb_quantize_pack_desc", "pb_quantize_pack_mode", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
-    "pb_matmul_bias_act", "pb_matmul_acc", "pb_matmul_acc_pairs", "pb_calib_mfma", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
+    "pb_matmul_static", "pb_matmul_bias_act", "pb_matmul_acc", "pb_matmul_acc_pairs", "pb_calib_mfma", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
 ]
 
 
@@ -75,6 +75,8 @@ def lib():
         L.pb_unpack.restype = _I
         L.pb_matmul.argtypes = [_P, _P, _D, _I, _P, _I, _P, _P, _P]
         L.pb_matmul.restype = _I
+        L.pb_matmul_static.argtypes = [_P, _P, _D, _I, _P, _I, _P, _P]
+        L.pb_matmul_static.restype = _I
         L.pb_matmul_bias_act.argtypes = [_P, _P, _D, _I, _P, _I, _P, _I, _P, _P, _P]
         L.pb_matmul_bias_act.restype = _I
         L.pb_matmul_acc.argtypes = [_P, _D, _I, _P, _I, _P, _P, _P]
@@ -188,6 +190,12 @@ def pb_matmul(packed, scales, d, bits_used, X, batch, Y, workspace, stream=None)
                            ctypes.byref(d), bits_used, _ptr(X, torch.float32, "X"), batch,
                            _ptr(Y, torch.float32, "Y"), _ptr(workspace, torch.uint8, "workspace"),
                            _stream(stream)), "pb_matmul")
+
+
+def pb_matmul_static(packed, scales, d, bits_used, X, batch, Y, stream=None):
+    _check(lib().pb_matmul_static(_ptr(packed, torch.uint8, "packed"), _ptr(scales, torch.float32, "scales"),
+                                  ctypes.byref(d), bits_used, _ptr(X, torch.float32, "X"), batch,
+                                  _ptr(Y, torch.float32, "Y"), _stream(stream)), "pb_matmul_static")
 
 
 def pb_matmul_bias_act(packed, scales, d, bits_used, X, batch, bias, act, Y, workspace, stream=None):
