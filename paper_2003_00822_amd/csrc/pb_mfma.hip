@@ -143,13 +143,38 @@ __device__ __forceinline__ int digit_of_row(int i) { return ((i & 7) << 1) | (i 
 // x_q (k-bit two's complement, sign-extended) -> the FP4 codes of its sixteen digits, nibble i = digit
 // digit_of_row(i); code = digit (value digit / 2), except for digit 15, the signed one (-2 b31 + b30: values
 // 0, 1, -2, -1 = codes 0000, 0001, 1010, 1001), which a byte table indexed by the two top bits supplies.
+// PK = 2, 4: x holds PK values of 32 / PK bits (activations of at most 16 / 8 bits, Section 3.1), each with its
+// own signed top digit: the nibbles of (E, O) are then the digits of PK vectors, 8 / PK even and 8 / PK odd ones each.
+template <int PK>
 __device__ __forceinline__ uint2 digit_codes(uint32_t x)
 {
     const uint32_t e = x & 0x33333333u;
     const uint32_t o = (x >> 2) & 0x33333333u;
-    // byte 3 of the selector x >> 6 is x >> 30: it picks the code (in the upper nibble) out of the table
-    const uint32_t top = __builtin_amdgcn_perm(0u, 0x90A01000u, x >> 6);
-    return make_uint2(e, (o & 0x0FFFFFFFu) | (top & 0xF0000000u));
+    // the top two bits of every value, as the low bits of a selector byte: byte 3 of x >> 6 is x >> 30, byte 1 the
+    // bits 15, 14, bytes 2 and 0 the bits 23, 22 and 7, 6 (under two more bits, masked away).  The selected table
+    // byte holds the code in its upper nibble.
+    constexpr uint32_t sel_mask = PK == 1 ? 0xFFFFFFFFu : PK == 2 ? 0x03000300u : 0x03030303u;
+    constexpr uint32_t keep = PK == 1 ? 0x0FFFFFFFu : PK == 2 ? 0x0FFF0FFFu : 0x0F0F0F0Fu;
+    uint32_t sel = x >> 6;
+    if constexpr (PK > 1) sel &= sel_mask;
+    const uint32_t top = __builtin_amdgcn_perm(0u, 0x90A01000u, sel);
+    return make_uint2(e, (o & keep) | (top & ~keep));
+}
+
+// PK values of 32 / PK bits (two's complement, already clamped to that range) in one word, value p in bits
+// 32 p / PK and up
+template <int PK>
+__device__ __forceinline__ uint32_t pack_values(const uint32_t (&v)[PK])
+{
+    if constexpr (PK == 1) {
+        return v[0];
+    } else if constexpr (PK == 2) {
+        return __builtin_amdgcn_perm(v[1], v[0], 0x05040100u);       // bytes a0 a1 b0 b1
+    } else {
+        const uint32_t ab = __builtin_amdgcn_perm(v[1], v[0], 0x0C0C0400u);   // bytes a0 b0 0 0
+        const uint32_t cd = __builtin_amdgcn_perm(v[3], v[2], 0x0C0C0400u);
+        return __builtin_amdgcn_perm(cd, ab, 0x05040100u);
+    }
 }
 
 // The 16 x 16 transpose of 4-bit elements that the LDS performs on a read (DS_READ_B64_TR_B4): in every group of
@@ -227,7 +252,10 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c, i
 // PAIR: a unit is a pair of bitlayers (worth it when several vectors share the expanded weights; with one vector
 // it measured 5-10 % slower up to 8192 columns and the same beyond: the stream starts later and a call has too few
 // units for the saved instructions to show).
-template <int NQ, int NV, int MAXS, int RU, bool PAIR>
+// PK: activation vectors per A operand.  With at most 16 (8) activation bits a vector has 8 (4) digits, the rest is
+// sign extension, so 2 (4) vectors share the sixteen rows of an operand and one instruction serves them all
+// (Section 3.1: fewer activation bits, less work).  NV then counts operands; a wave serves NV * PK vectors.
+template <int NQ, int NV, int MAXS, int RU, bool PAIR, int PK>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, const float *X0, uint32_t packed_bytes,
                                                     uint32_t flags, int cols0, int batch, uint32_t layer_step,
                                                     uint32_t round_step, int rounds_per_wg, int rt_count, int cq,
@@ -238,10 +266,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // the rest of the ring follows once the digit rows are built.
     // (two units measured best: with three or four a call of 4096 or 8192 columns takes 0.2-0.5 us longer)
     constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
-    // sums per vector, bitlayer (or pair), row and quarter of the digits (even 0-6, even 8-14, odd 1-7, odd 9-15: the
-    // four operand rows of a lane of the result; the 64 lanes of a wave add to 64 different words); two buffers, used
-    // by alternate row tiles
-    __shared__ __align__(16) int abuf[2][NV][PB_MAX_BITS][kTileRows][4];
+    static_assert(PK == 1 || PAIR, "packed vectors run on the pair kernels");
+    // sums per operand, bitlayer (or pair), row and kind of lane: the four operand rows of a lane of the result are
+    // the even digits 0-6, the even digits 8-14, the odd digits 1-7, the odd digits 9-15 of one vector (PK = 1); the
+    // even and the odd digits of two vectors (PK = 2: lanes kb = 0, 2 the first, kb = 1, 3 the second); with PK = 4 a
+    // lane holds two digits of each of two vectors and keeps two sums.  The 64 lanes of a wave add to different
+    // words.  Two buffers, used by alternate row tiles.
+    constexpr int QN = PK == 4 ? 8 : 4;
+    __shared__ __align__(16) int abuf[2][NV][PB_MAX_BITS][kTileRows][QN];
     __shared__ float s_scales[PB_MAX_BITS];
     // staging area of the activation transpose, kStageRows rows of 8 bytes per wave (none when the planes are given)
     extern __shared__ __align__(16) unsigned char stage_lds[];
@@ -249,7 +281,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = (h.cq + NQ - 1) / NQ;                    // = blockDim.x / 64 (the launcher's S), from a preloaded argument
-    const int n0 = blockIdx.y * NV;                             // first activation vector of this workgroup
+    const int n0 = blockIdx.y * NV * PK;                        // first activation vector of this workgroup
     const int m = h.m;
     const int q0 = wave * NQ;                                   // first chunk of this wave's column slice
     const int nq = min(NQ, h.cq - q0);                          // chunks it really has (>= 1 by construction)
@@ -314,7 +346,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // and before any wave requests weights: the memory pipeline of a CU returns data in request order, so an
     // activation load queued behind another wave's weight loads (HBM misses) would arrive a memory latency late.
     auto zero_sums_and_meet = [&]() {
-        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * 4 * kTileRows; i += nwaves * 64)
+        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * QN * kTileRows; i += nwaves * 64)
             (&abuf[0][0][0][0][0])[i] = 0;
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -326,7 +358,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const int kb = lane >> 4;
     u32x4 pa[NV][NQ][4];
     constexpr int VG = NV > 4 ? 4 : NV;   // vectors whose activations are in flight together
-    if (h.flags & kPlanesGiven) {
+    if (PK == 1 && (h.flags & kPlanesGiven)) {
         const uint32_t top = (lane & 15) == 15 ? 0x22222222u : 0u;
 #pragma unroll
         for (int g = 0; g < NV; g += VG) {
@@ -379,48 +411,58 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
         uint2 *const wr_row = stage + stage_row(lane >> 3, 0, lane & 7);   // a load's four columns: word 8 j + (lane >> 3), n = lane & 7
         const uint2 *const rd_row = stage + stage_row(4 * kb, (lane >> 3) & 1, lane & 7);
         const int col0 = 512 * q0 + 4 * lane;                 // first column of the lane's load j = 0 of chunk 0
+        // operands whose activations are in flight together (PK vectors each)
+        constexpr int VGP = PK >= VG ? 1 : VG / PK;
 #pragma unroll
-        for (int g = 0; g < NV; g += VG) {
-            u32x4 xv[VG][NQ][2];
+        for (int g = 0; g < NV; g += VGP) {
+            u32x4 xv[VGP][PK][NQ][2];
 #pragma unroll
-            for (int v = 0; v < VG; ++v) {
-                const int n = min(n0 + g + v, h.batch - 1);
-                const bool live = n0 + g + v < h.batch;
-                const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<float *>(h.X0 + (size_t)n * h.cols0), 0, live ? h.cols0 * 4 : 0, 0x00020000);
+            for (int v = 0; v < VGP; ++v)
 #pragma unroll
-                for (int q = 0; q < NQ; ++q)
+                for (int p = 0; p < PK; ++p) {
+                    const int nn = n0 + (g + v) * PK + p;
+                    const int n = min(nn, h.batch - 1);
+                    const bool live = nn < h.batch;
+                    const __amdgpu_buffer_rsrc_t rx0 = __builtin_amdgcn_make_buffer_rsrc(
+                        const_cast<float *>(h.X0 + (size_t)n * h.cols0), 0, live ? h.cols0 * 4 : 0, 0x00020000);
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        xv[v][q][j] = __builtin_amdgcn_raw_buffer_load_b128(rx0, (col0 + 512 * q + 256 * j) * 4, 0, 0);
-            }
+                    for (int q = 0; q < NQ; ++q)
+#pragma unroll
+                        for (int j = 0; j < 2; ++j)
+                            xv[v][p][q][j] =
+                                __builtin_amdgcn_raw_buffer_load_b128(rx0, (col0 + 512 * q + 256 * j) * 4, 0, 0);
+                }
             // Second part of a concatenated input [X0 ; X1].  Offsets of columns that belong to the first part
             // would be negative: they are clamped and the value dropped (a negative register offset that an
             // instruction offset brings back above zero is not range-checked lane by lane on this hardware).
             // If cols0 is a multiple of 4 a lane's four columns lie in one part and one 16-byte load serves;
             // else every column is loaded by itself.
-            u32x4 xw[VG][NQ][2];
+            u32x4 xw[VGP][PK][NQ][2];
             if (h.flags & kSecondPart) {
 #pragma unroll
-                for (int v = 0; v < VG; ++v) {
-                    const int n = min(n0 + g + v, h.batch - 1);
-                    const bool live = n0 + g + v < h.batch;
-                    const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
-                        const_cast<float *>(a.X1 + (size_t)n * a.cols1), 0, live ? a.cols1 * 4 : 0, 0x00020000);
+                for (int v = 0; v < VGP; ++v)
 #pragma unroll
-                    for (int q = 0; q < NQ; ++q)
+                    for (int p = 0; p < PK; ++p) {
+                        const int nn = n0 + (g + v) * PK + p;
+                        const int n = min(nn, h.batch - 1);
+                        const bool live = nn < h.batch;
+                        const __amdgpu_buffer_rsrc_t rx1 = __builtin_amdgcn_make_buffer_rsrc(
+                            const_cast<float *>(a.X1 + (size_t)n * a.cols1), 0, live ? a.cols1 * 4 : 0, 0x00020000);
 #pragma unroll
-                        for (int j = 0; j < 2; ++j) {
-                            const int c1 = col0 + 512 * q + 256 * j - h.cols0;
-                            if ((h.cols0 & 3) == 0) {
-                                xw[v][q][j] = __builtin_amdgcn_raw_buffer_load_b128(rx1, max(c1, 0) * 4, 0, 0);
-                            } else {
+                        for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                                for (int r = 0; r < 4; ++r)
-                                    xw[v][q][j][r] = __builtin_amdgcn_raw_buffer_load_b32(rx1, max(c1 + r, 0) * 4, 0, 0);
+                            for (int j = 0; j < 2; ++j) {
+                                const int c1 = col0 + 512 * q + 256 * j - h.cols0;
+                                if ((h.cols0 & 3) == 0) {
+                                    xw[v][p][q][j] = __builtin_amdgcn_raw_buffer_load_b128(rx1, max(c1, 0) * 4, 0, 0);
+                                } else {
+#pragma unroll
+                                    for (int r = 0; r < 4; ++r)
+                                        xw[v][p][q][j][r] =
+                                            __builtin_amdgcn_raw_buffer_load_b32(rx1, max(c1 + r, 0) * 4, 0, 0);
+                                }
                             }
-                        }
-                }
+                    }
             }
             if (g == 0) {
                 zero_sums_and_meet();
@@ -430,17 +472,20 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
             }
             if (h.flags & kSecondPart) {
 #pragma unroll
-                for (int v = 0; v < VG; ++v)
+                for (int v = 0; v < VGP; ++v)
 #pragma unroll
-                    for (int q = 0; q < NQ; ++q)
+                    for (int p = 0; p < PK; ++p)
 #pragma unroll
-                        for (int j = 0; j < 2; ++j)
+                        for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                            for (int r = 0; r < 4; ++r)
-                                xv[v][q][j][r] |= col0 + 512 * q + 256 * j + r >= h.cols0 ? xw[v][q][j][r] : 0u;
+                            for (int j = 0; j < 2; ++j)
+#pragma unroll
+                                for (int r = 0; r < 4; ++r)
+                                    xv[v][p][q][j][r] |=
+                                        col0 + 512 * q + 256 * j + r >= h.cols0 ? xw[v][p][q][j][r] : 0u;
             }
 #pragma unroll
-            for (int v = 0; v < VG; ++v)
+            for (int v = 0; v < VGP; ++v)
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     // (the reads of the chunk before have returned: their registers were waited for below)
@@ -448,9 +493,12 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                     for (int j = 0; j < 2; ++j)
 #pragma unroll
                         for (int r = 0; r < 4; ++r) {
-                            const uint32_t xq =
-                                (uint32_t)to_fixed_point(__uint_as_float(xv[v][q][j][r]), a.fscale, a.imin, a.imax);
-                            wr_row[stage_row(8 * j, r, 0)] = digit_codes(xq);
+                            uint32_t xq[PK];
+#pragma unroll
+                            for (int p = 0; p < PK; ++p)
+                                xq[p] = (uint32_t)to_fixed_point(__uint_as_float(xv[v][p][q][j][r]), a.fscale, a.imin,
+                                                                 a.imax);
+                            wr_row[stage_row(8 * j, r, 0)] = digit_codes<PK>(pack_values<PK>(xq));
                         }
                     // the wave's own writes have landed before its lanes read each other's rows
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
@@ -484,17 +532,27 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // of the four kinds of lanes stay apart until the row tile is finished.
     // Sums of digit products are <= 9 * 2048 (a slice has at most 2048 columns): c0 + 16 c1 and c2 + 16 c3 are exact
     // in fp32 (< 2^19), their combination is an integer below 2^27.
+    // With PK = 2 the same four registers are four digits (even or odd) of one of two vectors; with PK = 4 two
+    // digits of each of two vectors, and the lane keeps the two halves c0 + 16 c1, c2 + 16 c3 apart.
     const int wscale = (PAIR && merged) ? 128 : 127;
-    auto lane_sum = [](const v4f acc) {
+    constexpr int LS = PK == 4 ? 2 : 1;   // sums of a lane per operand
+    auto lane_sums = [](const v4f acc, int (&out)[LS]) {
         const float t0 = fmaf(acc[1], 16.0f, acc[0]), t1 = fmaf(acc[3], 16.0f, acc[2]);
-        return (int)t0 + ((int)t1 << 8);
+        if constexpr (PK == 4) {
+            out[0] = (int)t0;
+            out[1] = (int)t1;
+        } else {
+            out[0] = (int)t0 + ((int)t1 << 8);
+        }
     };
     const int j = lane & 15;
     // sum_c x_q[c] over the slice, as this lane's share of it in the form the sums below have (merged pairs only):
     // the product with an operand of digits 1
-    int sx[NV];
+    int sx[NV][LS];
 #pragma unroll
-    for (int v = 0; v < NV; ++v) sx[v] = 0;
+    for (int v = 0; v < NV; ++v)
+#pragma unroll
+        for (int e = 0; e < LS; ++e) sx[v][e] = 0;
     if (PAIR && merged && m >= 2) {
         const v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};
 #pragma unroll
@@ -504,15 +562,20 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc, wscale);
-            sx[v] = lane_sum(acc);
+            lane_sums(acc, sx[v]);
         }
     }
     int pp = 0, pr = 0;   // pair and round of the unit being multiplied
     // the end of a pass: the sums of this lane go to `set` in LDS
     auto finish = [&](const v4f (&acc)[NV], int set, bool sign_pair) {
 #pragma unroll
-        for (int v = 0; v < NV; ++v)   // (the digits of the sign pair stand 2 too high in every column)
-            atomicAdd(&abuf[pr & 1][v][set][j][kb], lane_sum(acc[v]) - (sign_pair ? 2 * sx[v] : 0));
+        for (int v = 0; v < NV; ++v) {
+            int ls[LS];
+            lane_sums(acc[v], ls);
+#pragma unroll
+            for (int e = 0; e < LS; ++e)   // (the digits of the sign pair stand 2 too high in every column)
+                atomicAdd(&abuf[pr & 1][v][set][j][LS * kb + e], ls[e] - (sign_pair ? 2 * sx[v][e] : 0));
+        }
     };
     for (int u0 = 0; u0 < U; u0 += RU) {
 #pragma unroll
@@ -568,55 +631,77 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                     pp = 0;
                     __syncthreads();
                     const int nsets = merged ? mp : m;
-                    constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per output
+                    constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per operand and row
                     constexpr int RW = (NV * LG * kTileRows + 63) / 64; // waves that one row tile's outputs occupy
                     for (int duty = (wave + nwaves - (pr * RW) % nwaves) % nwaves; duty < RW; duty += nwaves) {
                         const int slot = duty * 4 + (lane >> 4);
-                        const int v = slot / LG, lg = slot % LG, jrow = lane & 15, n = n0 + v;
+                        const int v = slot / LG, lg = slot % LG, jrow = lane & 15;
                         const int prow = (rt0 + pr) * kTileRows + jrow;
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
-                        const bool live = v < NV && n < h.batch && row >= 0 && row < a.R;
+                        const bool row_ok = v < NV && row >= 0 && row < a.R;
                         int4 *src = reinterpret_cast<int4 *>(&abuf[pr & 1][v < NV ? v : 0][lg][jrow][0]);
-                        double z = 0.0;
+                        double z[PK];
+#pragma unroll
+                        for (int p = 0; p < PK; ++p) z[p] = 0.0;
                         if (v < NV) {
-                            for (int i = lg; i < nsets; i += LG, src += LG * kTileRows) {
-                                // the quarters: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in units of 4^8, digits
-                                // 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below 2^31 in magnitude
-                                // (4369 * 9 * 32768 columns)
-                                const int4 q = *src;
-                                *src = make_int4(0, 0, 0, 0);
-                                const long long sum = (long long)q.x + 4 * (long long)q.z +
-                                                      (((long long)q.y + 4 * (long long)q.w) << 16);
-                                if (a.A) {
-                                    if (live) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
-                                } else {
-                                    // a merged pair carries the scale of its low bitlayer
-                                    const int si = !merged ? i : min(2 * i + 1, m - 1);
-                                    z = fma((double)s_scales[si], (double)sum, z);
+                            for (int i = lg; i < nsets; i += LG, src += LG * kTileRows * (QN / 4)) {
+                                // PK = 1, the quarters of one vector: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in
+                                // units of 4^8, digits 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below
+                                // 2^31 in magnitude (4369 * 9 * 32768 columns).  PK = 2, 4: even digits + 4 * odd digits
+                                // of vector p.
+                                int qv[QN];
+#pragma unroll
+                                for (int e = 0; e < QN / 4; ++e) {
+                                    const int4 t = src[e];
+                                    src[e] = make_int4(0, 0, 0, 0);
+                                    qv[4 * e] = t.x; qv[4 * e + 1] = t.y; qv[4 * e + 2] = t.z; qv[4 * e + 3] = t.w;
+                                }
+                                // a merged pair carries the scale of its low bitlayer
+                                const int si = !merged ? i : min(2 * i + 1, m - 1);
+#pragma unroll
+                                for (int p = 0; p < PK; ++p) {
+                                    const long long sum =
+                                        PK == 1 ? (long long)qv[0] + 4 * (long long)qv[2] +
+                                                      (((long long)qv[1] + 4 * (long long)qv[3]) << 16)
+                                                : (long long)qv[p] + 4 * (long long)qv[PK + p];
+                                    const int n = n0 + v * PK + p;
+                                    if (a.A) {
+                                        if (row_ok && n < h.batch) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
+                                    } else {
+                                        z[p] = fma((double)s_scales[si], (double)sum, z[p]);
+                                    }
                                 }
                             }
                         }
-                        if (LG >= 2) z = add_across<16>(z);
-                        if (LG == 4) z = add_across<32>(z);
+#pragma unroll
+                        for (int p = 0; p < PK; ++p) {
+                            if (LG >= 2) z[p] = add_across<16>(z[p]);
+                            if (LG == 4) z[p] = add_across<32>(z[p]);
+                        }
                         if (!a.A) {
-                            float y = (float)(z * a.out_scale);
-                            if (a.bias && live) y += a.bias[row];
-                            if (a.c_prev) {
-                                // LSTM cell: the four lanes of a quad hold the gates i, f, g, o of one unit (row = unit
-                                // for gate i); the first lane of the quad updates the unit
-                                const float gi = __uint_as_float(dpp_mov<0x00>(__float_as_uint(y)));
-                                const float gf = __uint_as_float(dpp_mov<0x55>(__float_as_uint(y)));
-                                const float gg = __uint_as_float(dpp_mov<0xAA>(__float_as_uint(y)));
-                                const float go = __uint_as_float(dpp_mov<0xFF>(__float_as_uint(y)));
-                                if ((lane & 3) == 0 && live && lg == 0) {
-                                    const size_t at = (size_t)n * a.gate_h + (size_t)row;
-                                    const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
-                                    a.c_out[at] = cn;
-                                    a.h_out[at] = sigmoid_f(go) * tanhf(cn);
+#pragma unroll
+                            for (int p = 0; p < PK; ++p) {
+                                const int n = n0 + v * PK + p;
+                                const bool live = row_ok && n < h.batch;
+                                float y = (float)(z[p] * a.out_scale);
+                                if (a.bias && live) y += a.bias[row];
+                                if (a.c_prev) {
+                                    // LSTM cell: the four lanes of a quad hold the gates i, f, g, o of one unit (row =
+                                    // unit for gate i); the first lane of the quad updates the unit
+                                    const float gi = __uint_as_float(dpp_mov<0x00>(__float_as_uint(y)));
+                                    const float gf = __uint_as_float(dpp_mov<0x55>(__float_as_uint(y)));
+                                    const float gg = __uint_as_float(dpp_mov<0xAA>(__float_as_uint(y)));
+                                    const float go = __uint_as_float(dpp_mov<0xFF>(__float_as_uint(y)));
+                                    if ((lane & 3) == 0 && live && lg == 0) {
+                                        const size_t at = (size_t)n * a.gate_h + (size_t)row;
+                                        const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
+                                        a.c_out[at] = cn;
+                                        a.h_out[at] = sigmoid_f(go) * tanhf(cn);
+                                    }
+                                } else {
+                                    if (a.relu) y = fmaxf(y, 0.0f);
+                                    if (live && lg == 0) a.Y[(size_t)n * a.R + row] = y;
                                 }
-                            } else {
-                                if (a.relu) y = fmaxf(y, 0.0f);
-                                if (live && lg == 0) a.Y[(size_t)n * a.R + row] = y;
                             }
                         }
                     }
@@ -628,15 +713,25 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     }
 }
 
-// The kernel variants: (chunks per wave, vectors per wave, most slices per workgroup, ring depth in units), each for
-// single bitlayers and for pairs.
+// The kernel variants: (chunks per wave, operands per wave, most slices per workgroup, ring depth in units), each for
+// single bitlayers, for pairs, and for pairs with two and four vectors per operand (fn[kind]; the variants with eight
+// operands have no kind 3: their sums would not fit the LDS).
 struct Variant {
     int nq, nv, maxs, ru;
-    const void *fn, *fn_pair;
+    const void *fn[4];
 };
-#define PB_VARIANT(NQ, NV, MAXS, RU)                                                      \
-    {NQ, NV, MAXS, RU, reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false>),   \
-     reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true>)}
+enum { kSingle = 0, kPairs = 1, kPairs2 = 2, kPairs4 = 3 };
+template <int NQ, int NV, int MAXS, int RU>
+static const void *pairs4_or_null()
+{
+    if constexpr (NV <= 4) return reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 4>);
+    else return nullptr;
+}
+#define PB_VARIANT(NQ, NV, MAXS, RU)                                                           \
+    {NQ, NV, MAXS, RU, {reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false, 1>),    \
+                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 1>),     \
+                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 2>),     \
+                        pairs4_or_null<NQ, NV, MAXS, RU>()}}
 static const Variant kVariants[] = {
     PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
     PB_VARIANT(1, 2, 16, 1), PB_VARIANT(1, 2, 16, 2), PB_VARIANT(1, 2, 16, 4),
@@ -678,13 +773,13 @@ static const Tuning &tuning()
 // As many vectors per wave as the batch has and the registers allow (each weight block is then read and expanded
 // once for all of them), then the smallest slice (most waves per row, shortest transpose per wave) whose slice
 // count fits a workgroup; ring depth 1 (the deeper rings are picked once the units per wave are known).
-static int pick_variant(const Layout &L, int batch)
+static int pick_variant(const Layout &L, int batch, int kind)
 {
     const int want_nq = tuning().nq, want_nv = tuning().nv;
     int best = -1;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
-        if (v.ru != 1) continue;
+        if (v.ru != 1 || !v.fn[kind]) continue;
         if ((L.cq + v.nq - 1) / v.nq > v.maxs) continue;
         if (want_nq && v.nq != want_nq) continue;
         if (want_nv ? v.nv != want_nv : (v.nv > 1 && v.nv / 2 >= batch)) continue;   // no more than one empty half
@@ -712,10 +807,10 @@ static size_t stage_bytes(int S) { return (size_t)S * kStageRows * sizeof(uint2)
 
 // Workgroups of S waves that fit on the device at once (occupancy does not change while the process lives, so it
 // is looked up once per kernel variant and workgroup size).
-static int resident_workgroups(int variant, int S, bool pair)
+static int resident_workgroups(int variant, int S, int kind)
 {
-    static int cache[2][kNumVariants][kMaxSlices + 1];
-    int *slot = &cache[pair ? 1 : 0][variant][S];
+    static int cache[4][kNumVariants][kMaxSlices + 1];
+    int *slot = &cache[kind][variant][S];
     int v = __atomic_load_n(slot, __ATOMIC_RELAXED);
     if (v > 0) return v;
     int dev = 0, cus = 0, per_cu = 0;
@@ -723,13 +818,13 @@ static int resident_workgroups(int variant, int S, bool pair)
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
     // (a workgroup's dynamic LDS may exceed the default limit of 64 KB, a compute unit of this chip has 160 KB:
     // declared for this variant and its siblings of other ring depths, one of which is the one launched)
-    const void *fn = pair ? kVariants[variant].fn_pair : kVariants[variant].fn;
+    const void *fn = kVariants[variant].fn[kind];
     if (stage_bytes(S) > 32 * 1024) {
         for (int i = 0; i < kNumVariants; ++i) {
             const Variant &o = kVariants[i];
             if (o.nq != kVariants[variant].nq || o.nv != kVariants[variant].nv || o.maxs != kVariants[variant].maxs)
                 continue;
-            if (hipFuncSetAttribute(pair ? o.fn_pair : o.fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+            if (hipFuncSetAttribute(o.fn[kind], hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)stage_bytes(S)) != hipSuccess)
                 return 0;
         }
@@ -764,21 +859,26 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.imax = (act_bits == 32) ? INT32_MAX : (int32_t)((1u << (act_bits - 1)) - 1u);
     a.imin = -a.imax - 1;
     a.out_scale = ldexp(1.0, -frac_bits);
-    int vi = pick_variant(L, batch);
+    // Vectors per operand: with at most 16 (8) activation bits two (four) vectors share an operand, if the call has
+    // that many (planes that are given in memory are taken one vector per operand).
+    int pk = planes ? 1 : (act_bits <= 8 ? 4 : (act_bits <= 16 ? 2 : 1));
+    while (pk > 1 && pk / 2 >= batch) pk /= 2;
+    const int slots = (batch + pk - 1) / pk;   // operands that the call fills
+    // Bitlayer pairs when several vectors share the expanded weights (and for the parity hook of the pairs); the
+    // kernels with packed operands are pair kernels (they multiply bitlayer by bitlayer when the per-layer sums are
+    // asked for or the scales do not halve)
+    bool pair = a.pairs_out || (!A && batch >= 2) || pk > 1;
+    if (tuning().pair >= 0 && pk == 1) pair = a.pairs_out || (!A && tuning().pair != 0);
+    if (L.cols > kMaxColsPairs) return (int)hipErrorInvalidValue;   // (cannot happen: pairs cover every width)
+    const int kind = !pair ? kSingle : (pk == 1 ? kPairs : (pk == 2 ? kPairs2 : kPairs4));
+    int vi = pick_variant(L, slots, kind);
     if (vi < 0) return (int)hipErrorInvalidValue;
     const Variant &var = kVariants[vi];   // (the ring depth does not change a variant's occupancy: same registers +- a few)
     const int S = (L.cq + var.nq - 1) / var.nq;
-    const int groups = (batch + var.nv - 1) / var.nv;
+    const int groups = (slots + var.nv - 1) / var.nv;
     // Workgroups: as many as are resident at once (so that every wave builds its planes once and the weight
     // stream never waits for a second round of workgroups to start), each with whole row tiles.
-    // Bitlayer pairs when several vectors share the expanded weights (and for the parity hook of the pairs)
-    bool pair = a.pairs_out || (!A && batch >= 2);
-    if (tuning().pair >= 0) pair = a.pairs_out || (!A && tuning().pair != 0);
-    if (L.cols > kMaxColsPairs) {
-        if (a.pairs_out) return (int)hipErrorInvalidValue;   // (the host API rejects this before)
-        pair = false;
-    }
-    int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S, pair);   // of the sibling that needs the most registers
+    int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S, kind);   // of the sibling that needs the most registers
     if (capacity < 1) return (int)hipErrorInvalidValue;
     if (tuning().wgs > 0) capacity = tuning().wgs;
     int wgs = capacity / groups;
@@ -789,8 +889,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     void *args[] = {&h.packed, &h.X0, &h.packed_bytes, &h.flags, &h.cols0, &h.batch, &h.layer_step, &h.round_step,
                     &h.rounds_per_wg, &h.rt_count, &h.cq, &h.m, &a};
     const Variant &run = kVariants[pick_ring(vi, h.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used))];
-    const hipError_t e = hipLaunchKernel(pair ? run.fn_pair : run.fn, dim3((unsigned)wgs, (unsigned)groups),
-                                         dim3((unsigned)S * 64), args, planes ? 0 : stage_bytes(S), st);
+    const hipError_t e = hipLaunchKernel(run.fn[kind], dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64),
+                                         args, planes ? 0 : stage_bytes(S), st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
 }
 

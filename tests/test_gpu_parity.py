@@ -272,6 +272,54 @@ def test_partial_sums_at_their_limits(pb, layout, cols):
             run_layer(pb, W, bits, X[n:n + 1], [2, 8], layout=layout)
 
 
+@pytest.mark.parametrize("fk", [(2, 4), (4, 8), (5, 9), (12, 16), (7, 12)])
+def test_vectors_that_share_an_operand(pb, fk):
+    """Activations of at most 16 (8) bits: two (four) vectors travel in one operand of the matrix-core kernel.
+    Batches that fill the operands and that leave sub-vectors or whole operands empty, every route (per-bitlayer
+    sums, pair sums, fp32 output), inputs that saturate at k bits."""
+    f, k = fk
+    for (R, C, N, case) in ((45, 1300, 2, 71), (33, 520, 3, 72), (20, 4200, 4, 73), (50, 300, 5, 74),
+                            (17, 9000, 9, 75), (40, 2100, 17, 76), (18, 700, 33, 77)):
+        print("shared operands", fk, R, C, N, flush=True)
+        W, X = synth.ragged(R, C, batch=N, case=case, xdist="wide" if case % 2 else "uniform")
+        run_layer(pb, W, 5, X, [1, 2, 5], frac_bits=f, act_bits=k, layout=LAYOUTS["mfma"])
+
+
+@pytest.mark.parametrize("k", [8, 16])
+def test_shared_operands_at_their_limits(pb, k):
+    """All-ones / all-qmax bitlayers times activations saturated at k bits, 32768 columns, batches of 4 and 5."""
+    cols, bits = 32768, 8
+    X = limit_vectors(cols)                     # +-40000 saturate at +-2^(k-1) with frac_bits = k - 2
+    for name, W in limit_matrices(cols, bits):
+        print("shared operands at the limits", k, name, flush=True)
+        run_layer(pb, W, bits, X, [2, 7, 8], frac_bits=k - 2, act_bits=k, layout=LAYOUTS["mfma"])
+        run_layer(pb, W, bits, X[:4], [8], frac_bits=k - 2, act_bits=k, layout=LAYOUTS["mfma"])
+
+
+def test_lstm_cell_with_narrow_activations_and_batch(pb):
+    """The fused cell update on operands that several vectors share (act_bits = 8, batch 6)."""
+    H, I, bits, N = 37, 100, 4, 6
+    g = np.random.default_rng(200300822 + 47)
+    W = g.uniform(-0.04, 0.04, size=(4 * H, I + H)).astype(np.float32)
+    x = g.normal(size=(N, I)).astype(np.float32)
+    h = g.uniform(-1, 1, size=(N, H)).astype(np.float32)
+    c = g.uniform(-1, 1, size=(N, H)).astype(np.float32)
+    bias = g.normal(0, 0.1, size=4 * H).astype(np.float32)
+    prep = po.prepare(W, bits)
+    lw = po.pack_words(prep["layers"])
+    xh = np.concatenate([x, h], axis=1)
+    _, Y = po.matmul_words(lw, prep["scales"], bits, I + H, xh, frac_bits=5, act_bits=8)
+    h_ref, c_ref = po.lstm_pointwise(Y, bias, c)
+    for lay in (GATES, LAYOUTS["mfma"]):
+        lin = pb.PackedLinear(dev(W), bits, max_batch=N, frac_bits=5, act_bits=8, layout=lay)
+        h_out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        c_out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        pb.pb_lstm_cell(lin.packed, lin.scales, lin.desc, bits, dev(x), I, dev(h), dev(c), dev(bias), h_out, c_out, N,
+                        lin.workspace)
+        assert np.abs(h_out.cpu().numpy() - h_ref).max() <= 2e-6
+        assert np.abs(c_out.cpu().numpy() - c_ref).max() <= 2e-6
+
+
 def test_reduced_activation_precision(pb, layout):
     # Section 3.1: k (activation precision) of 8 or 16 planes; the fixed point moves with it
     W, X = synth.ragged(50, 300, batch=2, case=5, xdist="uniform")
