@@ -312,6 +312,13 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const uint32_t avail = (uint32_t)(h.packed_bytes - base_off);
     const int voff = lane * 16;
     constexpr int SB = PAIR ? 2 * NQ : NQ;   // blocks of a unit
+    // Cache policy of the weight loads: streaming (non-temporal) where a call reads every block once; the pair
+    // kernels serve batches, whose vector groups read the same blocks at about the same time on one XCD and should
+    // find them in its L2.
+#ifndef PB_WEIGHT_POLICY_PAIR
+#define PB_WEIGHT_POLICY_PAIR 0
+#endif
+    constexpr int kWeightPolicy = PAIR ? PB_WEIGHT_POLICY_PAIR : 2;
     u32x4 ring[RU][SB];
     uint32_t ld_round = 0;
     int ld_p = 0, ld_u = 0;
@@ -327,14 +334,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
         for (int q = 0; q < NQ; ++q) {
             const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                 const_cast<char *>(base), 0, (ld_u < U && q < nq) ? (int)avail : 0, 0x00020000);
-            dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)lo_off, /*nt*/ 2);
+            dst[q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)lo_off, kWeightPolicy);
         }
         if constexpr (PAIR) {
 #pragma unroll
             for (int q = 0; q < NQ; ++q) {
                 const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
                     const_cast<char *>(base), 0, (ld_u < U && has_hi && q < nq) ? (int)avail : 0, 0x00020000);
-                dst[NQ + q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)hi_off, /*nt*/ 2);
+                dst[NQ + q] = __builtin_amdgcn_raw_buffer_load_b128(rs, voff + q * 1024, (int)hi_off, kWeightPolicy);
             }
         }
         __builtin_amdgcn_sched_barrier(0x7);
