@@ -57,6 +57,9 @@ def parse():
                     help="only the batched workload at one point: --size x --size (use 8192), bits_used = --bits, N "
                          "vectors, --steps calls (the run the batched profiler summaries are made from; prints its own "
                          "small JSON line, not the headline one)")
+    ap.add_argument("--models-only", action="store_true",
+                    help="only the MLP forward and the LSTM sequence (the run the profiler summaries of the layer "
+                         "sequences are made from; prints its own small JSON line)")
     ap.add_argument("--calib", action="store_true",
                     help="also launch a plain elementwise kernel that reads and writes 256 MiB (reference for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this command)")
@@ -83,6 +86,9 @@ def main():
     if args.batch_point:
         print(json.dumps(batch_point(torch, pb, synth, dev, n, B, args.batch_point, args.steps, args.layout)),
               flush=True)
+        return
+    if args.models_only:
+        print(json.dumps(model_sequences(torch, pb, synth, dev)), flush=True)
         return
     std = {4096: 0.02, 8192: 0.01}.get(n, 0.01)
     W, X = synth.fc_square(n, std, batch=1, cfg=2 if n == 4096 else 5)

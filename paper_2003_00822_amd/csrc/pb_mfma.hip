@@ -49,6 +49,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "pb_kernels.h"
 
 namespace pb {
@@ -94,12 +96,14 @@ struct MfmaArgs {
 
 // x_q = Int(x * 2^f) as a k-bit two's-complement value: toward zero, saturating, NaN -> 0.  V_CVT_I32_F32 does
 // exactly that for k = 32 (out-of-range inputs saturate, NaN converts to 0); narrower k clamp the integer.
+template <bool NARROW>
 __device__ __forceinline__ int32_t to_fixed_point(float x, float fscale, int32_t imin, int32_t imax)
 {
     int32_t r;
     const float p = x * fscale;   // exact: a power of two
     asm("v_cvt_i32_f32 %0, %1" : "=v"(r) : "v"(p));
-    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(r), "v"(imin), "v"(imax));   // imin <= imax: the clamp
+    if constexpr (NARROW)
+        asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(r), "v"(imin), "v"(imax));   // imin <= imax: the clamp
     return r;
 }
 
@@ -496,17 +500,22 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
 #pragma unroll
                 for (int q = 0; q < NQ; ++q) {
                     // (the reads of the chunk before have returned: their registers were waited for below)
+                    // (32-bit activations need no clamp after the conversion: one instruction less per value)
+                    auto write_rows = [&](auto narrow) {
 #pragma unroll
-                    for (int j = 0; j < 2; ++j)
+                        for (int j = 0; j < 2; ++j)
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            uint32_t xq[PK];
+                            for (int r = 0; r < 4; ++r) {
+                                uint32_t xq[PK];
 #pragma unroll
-                            for (int p = 0; p < PK; ++p)
-                                xq[p] = (uint32_t)to_fixed_point(__uint_as_float(xv[v][p][q][j][r]), a.fscale, a.imin,
-                                                                 a.imax);
-                            wr_row[stage_row(8 * j, r, 0)] = digit_codes<PK>(pack_values<PK>(xq));
-                        }
+                                for (int p = 0; p < PK; ++p)
+                                    xq[p] = (uint32_t)to_fixed_point<decltype(narrow)::value>(
+                                        __uint_as_float(xv[v][p][q][j][r]), a.fscale, a.imin, a.imax);
+                                wr_row[stage_row(8 * j, r, 0)] = digit_codes<PK>(pack_values<PK>(xq));
+                            }
+                    };
+                    if (PK > 1 || a.imin != INT32_MIN) write_rows(std::true_type{});
+                    else write_rows(std::false_type{});
                     // the wave's own writes have landed before its lanes read each other's rows
                     asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
                     __builtin_amdgcn_wave_barrier();
@@ -796,7 +805,9 @@ static int pick_variant(const Layout &L, int batch, int kind)
     return best;
 }
 
-// The sibling of variant `vi` with the deepest ring that a wave with `units` units fills.
+// The sibling of variant `vi` with the deepest ring that a wave with `units` units fills; with three units and
+// rings of 2 and 4 to choose from, the deeper one (a wave with one or two units is faster without empty ring slots,
+// one with three is 0.2 us faster when all three are in flight).
 static int pick_ring(int vi, int units)
 {
     const int want = tuning().ru;
@@ -804,7 +815,8 @@ static int pick_ring(int vi, int units)
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
         if (v.nq != kVariants[vi].nq || v.nv != kVariants[vi].nv || v.maxs != kVariants[vi].maxs) continue;
-        if (want ? v.ru == want : (v.ru <= units && v.ru > kVariants[best].ru)) best = i;
+        const int cap = units == 3 ? 4 : units;
+        if (want ? v.ru == want : (v.ru <= cap && v.ru > kVariants[best].ru)) best = i;
     }
     return best;
 }
