@@ -70,7 +70,7 @@ def parse():
 def main():
     args = parse()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the path shards by output rows across GPUs, see DESIGN.md); "
+        print("bench.py: this build runs on ONE GPU (across GPUs the path would shard by output rows); "
               "--gpus %d is not supported, use --gpus 1" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import numpy as np
