@@ -317,12 +317,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const int voff = lane * 16;
     constexpr int SB = PAIR ? 2 * NQ : NQ;   // blocks of a unit
     // Cache policy of the weight loads: streaming (non-temporal) where a call reads every block once; the pair
-    // kernels serve batches, whose vector groups read the same blocks at about the same time on one XCD and should
-    // find them in its L2.
-#ifndef PB_WEIGHT_POLICY_PAIR
-#define PB_WEIGHT_POLICY_PAIR 0
-#endif
-    constexpr int kWeightPolicy = PAIR ? PB_WEIGHT_POLICY_PAIR : 2;
+    // kernels with four and more operands serve batches, whose vector groups read the same blocks at about the same
+    // time on one XCD and should find them in its L2.  (Pair kernels with one or two operands run as a single
+    // group: streaming measured 20 % faster there with two vectors.)
+    constexpr int kWeightPolicy = (PAIR && NV > 2) ? 0 : 2;
     u32x4 ring[RU][SB];
     uint32_t ld_round = 0;
     int ld_p = 0, ld_u = 0;
@@ -659,12 +657,12 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         double z[PK];
 #pragma unroll
                         for (int p = 0; p < PK; ++p) z[p] = 0.0;
-                        if (v < NV) {
-                            for (int i = lg; i < nsets; i += LG, src += LG * kTileRows * (QN / 4)) {
-                                // PK = 1, the quarters of one vector: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in
-                                // units of 4^8, digits 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below
-                                // 2^31 in magnitude (4369 * 9 * 32768 columns).  PK = 2, 4: even digits + 4 * odd digits
-                                // of vector p.
+                        // PK = 1, the quarters of one vector: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in units
+                        // of 4^8, digits 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below 2^31 in
+                        // magnitude (4369 * 9 * 32768 columns).  PK = 2, 4: even digits + 4 * odd digits of vector p.
+                        constexpr int SET = kTileRows * (QN / 4);   // int4s from one set of sums to the next
+                        if (v < NV && a.A) {
+                            for (int i = lg; i < nsets; i += LG, src += LG * SET) {
                                 int qv[QN];
 #pragma unroll
                                 for (int e = 0; e < QN / 4; ++e) {
@@ -672,8 +670,6 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                     src[e] = make_int4(0, 0, 0, 0);
                                     qv[4 * e] = t.x; qv[4 * e + 1] = t.y; qv[4 * e + 2] = t.z; qv[4 * e + 3] = t.w;
                                 }
-                                // a merged pair carries the scale of its low bitlayer
-                                const int si = !merged ? i : min(2 * i + 1, m - 1);
 #pragma unroll
                                 for (int p = 0; p < PK; ++p) {
                                     const long long sum =
@@ -681,10 +677,45 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                                       (((long long)qv[1] + 4 * (long long)qv[3]) << 16)
                                                 : (long long)qv[p] + 4 * (long long)qv[PK + p];
                                     const int n = n0 + v * PK + p;
-                                    if (a.A) {
-                                        if (row_ok && n < h.batch) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
-                                    } else {
-                                        z[p] = fma((double)s_scales[si], (double)sum, z[p]);
+                                    if (row_ok && n < h.batch) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
+                                }
+                            }
+                        } else if (v < NV) {
+                            // The sets of a lane are read CH at a time, together with their scales, so that the LDS
+                            // latency is paid once: sets beyond the last one hold zeros (nothing ever adds to them) and
+                            // add nothing.  The 32-bit parts convert to fp64 exactly and so does their combination
+                            // (below 2^51), which is the integer sum itself.
+                            constexpr int MAXI = PB_MAX_BITS / LG;   // sets a lane can have
+                            constexpr int CH = LG == 4 ? 2 : 4;      // (a chunk covers eight sets, or four)
+                            static_assert(MAXI % CH == 0, "whole chunks");
+                            for (int k0 = 0; k0 * LG < nsets; k0 += CH, src += CH * LG * SET) {
+                                int4 t[CH][QN / 4];
+                                float sc[CH];
+#pragma unroll
+                                for (int c = 0; c < CH; ++c) {
+                                    const int i = lg + LG * (k0 + c);          // < PB_MAX_BITS
+#pragma unroll
+                                    for (int e = 0; e < QN / 4; ++e) t[c][e] = src[c * LG * SET + e];
+                                    // a merged pair carries the scale of its low bitlayer
+                                    sc[c] = s_scales[!merged ? i : min(2 * i + 1, m - 1)];
+                                }
+#pragma unroll
+                                for (int c = 0; c < CH; ++c)
+#pragma unroll
+                                    for (int e = 0; e < QN / 4; ++e) src[c * LG * SET + e] = make_int4(0, 0, 0, 0);
+#pragma unroll
+                                for (int c = 0; c < CH; ++c) {
+                                    double qd[QN];
+#pragma unroll
+                                    for (int e = 0; e < QN / 4; ++e) {
+                                        qd[4 * e] = (double)t[c][e].x; qd[4 * e + 1] = (double)t[c][e].y;
+                                        qd[4 * e + 2] = (double)t[c][e].z; qd[4 * e + 3] = (double)t[c][e].w;
+                                    }
+#pragma unroll
+                                    for (int p = 0; p < PK; ++p) {
+                                        const double sum = PK == 1 ? fma(65536.0, fma(4.0, qd[3], qd[1]), fma(4.0, qd[2], qd[0]))
+                                                                   : fma(4.0, qd[PK + p], qd[p]);
+                                        z[p] = fma((double)sc[c], sum, z[p]);
                                     }
                                 }
                             }
