@@ -42,6 +42,10 @@ constexpr int kMaxColsTile16 = 32768;     // 16 slices of 2048 columns
 // merged bitlayer pairs (digit products up to 9): a quarter sum stays below 4369 * 9 * 32768 < 2^31, so pairs cover
 // every width the tiled layouts have
 constexpr int kMaxColsPairs = 32768;
+// Bitlayer pairs whose sums the matrix-core kernel accumulates in one set of registers (pair p of a group counts
+// 4^(last - p)): with five, a register stays below 9 * 2048 * 341 < 2^24 and the half sums of a row below
+// 17 * 9 * 32768 * 341 < 2^31.
+constexpr int kPairGroup = 5;
 
 struct Layout {
     uint32_t layout;

@@ -27,8 +27,10 @@
 // (2, 3), ... and a last single bitlayer if bits_used is odd.  The sign bitlayer has the scale -2 s_1, so its
 // pair needs the digit w_1 - 2 w_0 = (2 (1 - w_0) + w_1) - 2: the bits of bitlayer 0 are complemented and
 // 2 * sum_c x_q[c] is subtracted, a sum that one more chain of instructions against an operand of digits 1
-// delivers once per call.  The kernel checks scales[0] == -2 scales[1], scales[2p] == 2 scales[2p + 1] itself and
-// multiplies bitlayer by bitlayer when that does not hold (any other scales are legal input).
+// delivers once per call.  Pair p then counts 4 times pair p + 1: the block scale of the weight operand (a power
+// of two per instruction) supplies that factor, and up to five pairs of a row tile add up in the same registers.
+// The kernel checks scales[0] == -2 scales[1], scales[i] == 2 scales[i + 1] itself and multiplies bitlayer by
+// bitlayer when that does not hold (any other scales are legal input).
 //
 // Operands.  A (16 x 128) = 16 digit rows x 128 columns, B (128 x 16) = 128 columns x
 // 16 weight rows, D (16 x 16): lane l of D holds row j = l % 16 of the weights and
@@ -240,12 +242,13 @@ __device__ __forceinline__ v8i weight_digit_operand(uint32_t hi, uint32_t lo)
     return as_operand(d);
 }
 
-// cbsz = blgp = 4: both operands FP4 (E2M1).  `scale` is the E8M0 block scale of both operands: 127 = 2^0 for a
-// weight operand of codes 2.0 (product = digit / 2 * 2), 128 = 2^1 for a weight operand of digits (product =
-// 2 digit / 2 * 2 digit / 2 = digit * digit), so that the sums are the integers themselves.
-__device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c, int scale)
+// cbsz = blgp = 4: both operands FP4 (E2M1).  `scale_a`, `scale_b` are the E8M0 block scales of the operands: 127 =
+// 2^0 on both sides for a weight operand of codes 2.0 (product = digit / 2 * 2), 128 = 2^1 on both sides for a weight
+// operand of digits (product = 2 digit / 2 * 2 digit / 2 = digit * digit), so that the sums are the integers
+// themselves; 128 + e on the weight side multiplies the products of one instruction by 2^e.
+__device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c, int scale_a, int scale_b)
 {
-    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, scale, 0, scale);
+    return __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(a, b, c, 4, 4, 0, scale_a, 0, scale_b);
 }
 
 // NQ: chunks of 512 columns per wave; NV: activation vectors whose digit rows a wave keeps (each weight block is
@@ -530,11 +533,11 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
         }
     }
     if (wave == 0 && lane < PB_MAX_BITS) s_scales[lane] = scv;
-    // pairs are merged if every pair's scales are in the ratio 2, -2 for the sign bitlayer (then
-    // s_hi A_hi + s_lo A_lo = s_lo (+-2 A_hi + A_lo))
+    // Pairs are merged if every scale is half the one before, minus half for the one after the sign bitlayer (then
+    // s_hi A_hi + s_lo A_lo = s_lo (+-2 A_hi + A_lo), and the pairs of a row tile are in the ratio 4 to each other)
     bool merged = PAIR && a.pairs_out != 0;
     if (PAIR && !a.A) {
-        const bool off = !(lane & 1) && lane + 1 < m && !(scv == (lane == 0 ? -2.0f : 2.0f) * scn);
+        const bool off = lane + 1 < m && !(scv == (lane == 0 ? -2.0f : 2.0f) * scn);
         merged = __builtin_amdgcn_ballot_w64(off) == 0;
     }
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
@@ -544,11 +547,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // The four registers of a lane of the result are the operand rows 4 kb + c: the digits b, b + 2, b + 4, b + 6
     // with b = 0, 8, 1, 9 for kb = 0 .. 3.  A lane adds them up with the weights 16^c (in units of 4^b) and the sums
     // of the four kinds of lanes stay apart until the row tile is finished.
-    // Sums of digit products are <= 9 * 2048 (a slice has at most 2048 columns): c0 + 16 c1 and c2 + 16 c3 are exact
-    // in fp32 (< 2^19), their combination is an integer below 2^27.
+    // Bitlayer by bitlayer: sums of digit products are <= 9 * 2048 (a slice has at most 2048 columns): c0 + 16 c1 and
+    // c2 + 16 c3 are exact in fp32 (< 2^19), their combination is an integer below 2^27.
     // With PK = 2 the same four registers are four digits (even or odd) of one of two vectors; with PK = 4 two
     // digits of each of two vectors, and the lane keeps the two halves c0 + 16 c1, c2 + 16 c3 apart.
-    const int wscale = (PAIR && merged) ? 128 : 127;
     constexpr int LS = PK == 4 ? 2 : 1;   // sums of a lane per operand
     auto lane_sums = [](const v4f acc, int (&out)[LS]) {
         const float t0 = fmaf(acc[1], 16.0f, acc[0]), t1 = fmaf(acc[3], 16.0f, acc[2]);
@@ -560,35 +562,62 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
         }
     };
     const int j = lane & 15;
-    // sum_c x_q[c] over the slice, as this lane's share of it in the form the sums below have (merged pairs only):
-    // the product with an operand of digits 1
-    int sx[NV][LS];
+    int pp = 0, pr = 0;   // pair and round of the unit being multiplied
+    // the end of a pass: the sums of this lane go to `set` in LDS
+    auto finish = [&](const v4f (&acc)[NV], int set) {
 #pragma unroll
-    for (int v = 0; v < NV; ++v)
+        for (int v = 0; v < NV; ++v) {
+            int ls[LS];
+            lane_sums(acc[v], ls);
 #pragma unroll
-        for (int e = 0; e < LS; ++e) sx[v][e] = 0;
+            for (int e = 0; e < LS; ++e) atomicAdd(&abuf[pr & 1][v][set][j][LS * kb + e], ls[e]);
+        }
+    };
+    // Merged pairs: the pairs of a row tile accumulate in ONE set of registers.  With all scales halving, pair p
+    // counts 2^e times the last pair of its group (e = the distance between their low bitlayers), and the block scale
+    // of the weight operand supplies that factor: a group of up to kPairGroup pairs costs one conversion and one LDS
+    // update instead of one per pair.  Bounds: a register holds at most 9 * 2048 * (1 + 4 + .. + 4^4) = 6.3 M < 2^24
+    // (exact in fp32); the two halves c0 + 16 c1 and c2 + 16 c3 of a lane are integers of their own in LDS, over the
+    // slices of a row at most 17 * 9 * 32768 * 341 = 1.71e9 < 2^31.
+    // (With the sums of the pairs asked for, a group is one pair.)
+    const int gsize = a.pairs_out ? 1 : kPairGroup;
+    auto low_layer = [&](int unit) { return min(2 * unit + 1, m - 1); };   // of a unit of a pair kernel
+    // sum_c x_q[c] over the slice, as this lane's share of it in the form of the group sums: the product with an
+    // operand of digits 1, doubled (the digits of the sign pair stand 2 too high in every column) and with the
+    // factor of pair 0 in its group
+    int sxc[NV][2];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) sxc[v][0] = sxc[v][1] = 0;
     if (PAIR && merged && m >= 2) {
         const v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};
+        const int e0 = low_layer(min(gsize, mp) - 1) - 1 + 1;   // (+ 1: doubled)
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             v4f acc = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
-                for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc, wscale);
-            lane_sums(acc, sx[v]);
+                for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc, 128, 128);
+            sxc[v][0] = ((int)acc[0] + ((int)acc[1] << 4)) << e0;
+            sxc[v][1] = ((int)acc[2] + ((int)acc[3] << 4)) << e0;
         }
     }
-    int pp = 0, pr = 0;   // pair and round of the unit being multiplied
-    // the end of a pass: the sums of this lane go to `set` in LDS
-    auto finish = [&](const v4f (&acc)[NV], int set, bool sign_pair) {
+    v4f accg[NV];         // the sums of the group being multiplied
+    int gfirst = 0, gset = 0;   // its first pair, its index in the row tile
+    // the end of a group: its sums go to LDS, eight integers per (operand, group, row): word 2 kb + e is the half e
+    // of the lanes of kind kb
+    auto finish_group = [&](bool sign_group) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            int ls[LS];
-            lane_sums(acc[v], ls);
-#pragma unroll
-            for (int e = 0; e < LS; ++e)   // (the digits of the sign pair stand 2 too high in every column)
-                atomicAdd(&abuf[pr & 1][v][set][j][LS * kb + e], ls[e] - (sign_pair ? 2 * sx[v][e] : 0));
+            int i0 = (int)accg[v][0] + ((int)accg[v][1] << 4);
+            int i1 = (int)accg[v][2] + ((int)accg[v][3] << 4);
+            if (sign_group) {
+                i0 -= sxc[v][0];
+                i1 -= sxc[v][1];
+            }
+            int *dst = &abuf[pr & 1][v][0][0][0] + gset * (kTileRows * 8) + j * 8 + 2 * kb;
+            atomicAdd(dst, i0);
+            atomicAdd(dst + 1, i1);
         }
     };
     for (int u0 = 0; u0 < U; u0 += RU) {
@@ -599,9 +628,12 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                 const bool has_hi = PAIR && 2 * pp + 1 <= m - 1;
                 // (chunks beyond a ragged last slice, and the absent high bitlayer of a single unit, are zero words)
                 if (PAIR && merged) {
-                    v4f acc[NV];
+                    if (pp == gfirst) {
 #pragma unroll
-                    for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                        for (int v = 0; v < NV; ++v) accg[v] = v4f{0.f, 0.f, 0.f, 0.f};
+                    }
+                    const int glast = min(gfirst + gsize, mp) - 1;             // last pair of this group
+                    const int bscale = 128 + low_layer(glast) - lo_layer;     // 2^1 for the digits, 2^e for the pair
                     const bool sign_pair = pp == 0 && has_hi;
                     const uint32_t inv = sign_pair ? 0xFFFFFFFFu : 0u;   // the sign bitlayer enters as 1 - w
 #pragma unroll
@@ -611,10 +643,15 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         for (int t = 0; t < 4; ++t) {
                             const v8i b = weight_digit_operand(wh[t], wl[t]);
 #pragma unroll
-                            for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v], wscale);
+                            for (int v = 0; v < NV; ++v)
+                                accg[v] = mfma_fp4(as_operand(pa[v][q][t]), b, accg[v], 128, bscale);
                         }
                     }
-                    finish(acc, pp, sign_pair);
+                    if (pp == glast) {
+                        finish_group(gfirst == 0 && m >= 2);
+                        gfirst += gsize;
+                        ++gset;
+                    }
                 } else {
 #pragma unroll
                     for (int h = PAIR ? 1 : 0; h >= 0; --h) {
@@ -629,10 +666,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                             for (int t = 0; t < 4; ++t) {
                                 const v8i b = weight_operand(w[t]);
 #pragma unroll
-                                for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v], wscale);
+                                for (int v = 0; v < NV; ++v) acc[v] = mfma_fp4(as_operand(pa[v][q][t]), b, acc[v], 127, 127);
                             }
                         }
-                        finish(acc, lo_layer - h, false);
+                        finish(acc, lo_layer - h);
                     }
                 }
                 if (++pp == mp) {
@@ -643,8 +680,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                     // bitlayers: scaled sums in fp64, then the sum over those lanes (rows of 16 lanes 16 or 32 apart).
                     // The waves take turns, so that none of them is always late for the next barrier.
                     pp = 0;
+                    gfirst = gset = 0;
                     __syncthreads();
-                    const int nsets = merged ? mp : m;
+                    const int nsets = merged ? (mp + gsize - 1) / gsize : m;
                     constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per operand and row
                     constexpr int RW = (NV * LG * kTileRows + 63) / 64; // waves that one row tile's outputs occupy
                     for (int duty = (wave + nwaves - (pr * RW) % nwaves) % nwaves; duty < RW; duty += nwaves) {
@@ -657,65 +695,102 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         double z[PK];
 #pragma unroll
                         for (int p = 0; p < PK; ++p) z[p] = 0.0;
-                        // PK = 1, the quarters of one vector: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in units
-                        // of 4^8, digits 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below 2^31 in
-                        // magnitude (4369 * 9 * 32768 columns).  PK = 2, 4: even digits + 4 * odd digits of vector p.
-                        constexpr int SET = kTileRows * (QN / 4);   // int4s from one set of sums to the next
-                        if (v < NV && a.A) {
-                            for (int i = lg; i < nsets; i += LG, src += LG * SET) {
-                                int qv[QN];
-#pragma unroll
-                                for (int e = 0; e < QN / 4; ++e) {
-                                    const int4 t = src[e];
-                                    src[e] = make_int4(0, 0, 0, 0);
-                                    qv[4 * e] = t.x; qv[4 * e + 1] = t.y; qv[4 * e + 2] = t.z; qv[4 * e + 3] = t.w;
-                                }
+                        if (PAIR && merged) {
+                            // group sums: the halves (i0, i1) of the four kinds of lanes; Q_kb = i0 + 256 i1 is what a
+                            // lane of kind kb would have had in one word
+                            int *grp = &abuf[pr & 1][v < NV ? v : 0][0][0][0] + jrow * 8;
+                            for (int g = lg; v < NV && g < nsets; g += LG) {
+                                int4 *g4 = reinterpret_cast<int4 *>(grp + g * (kTileRows * 8));
+                                const int4 t0 = g4[0], t1 = g4[1];
+                                g4[0] = g4[1] = make_int4(0, 0, 0, 0);
+                                const int w[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+                                // the group carries the scale of the low bitlayer of its last pair
+                                const int si = low_layer(min((g + 1) * gsize, mp) - 1);
 #pragma unroll
                                 for (int p = 0; p < PK; ++p) {
-                                    const long long sum =
-                                        PK == 1 ? (long long)qv[0] + 4 * (long long)qv[2] +
-                                                      (((long long)qv[1] + 4 * (long long)qv[3]) << 16)
-                                                : (long long)qv[p] + 4 * (long long)qv[PK + p];
                                     const int n = n0 + v * PK + p;
-                                    if (row_ok && n < h.batch) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
+                                    if (a.A) {
+                                        long long Q[4];
+#pragma unroll
+                                        for (int c = 0; c < 4; ++c) Q[c] = (long long)w[2 * c] + 256 * (long long)w[2 * c + 1];
+                                        const long long sum = PK == 1   ? Q[0] + 4 * Q[2] + ((Q[1] + 4 * Q[3]) << 16)
+                                                              : PK == 2 ? Q[p] + 4 * Q[2 + p]
+                                                                        : (long long)w[p] + 4 * (long long)w[4 + p];
+                                        if (row_ok && n < h.batch) a.A[((size_t)g * h.batch + n) * (size_t)a.R + row] = sum;
+                                    } else {
+                                        // (every part converts exactly; the last step rounds once if the sum is
+                                        // beyond 2^53, as the conversion of the 64-bit integer would)
+                                        double Q[4];
+#pragma unroll
+                                        for (int c = 0; c < 4; ++c) Q[c] = fma(256.0, (double)w[2 * c + 1], (double)w[2 * c]);
+                                        const double sum = PK == 1   ? fma(65536.0, fma(4.0, Q[3], Q[1]), fma(4.0, Q[2], Q[0]))
+                                                           : PK == 2 ? fma(4.0, Q[2 + p], Q[p])
+                                                                     : fma(4.0, (double)w[4 + p], (double)w[p]);
+                                        z[p] = fma((double)s_scales[si], sum, z[p]);
+                                    }
                                 }
                             }
-                        } else if (v < NV) {
-                            // The sets of a lane are read CH at a time, together with their scales, so that the LDS
-                            // latency is paid once: sets beyond the last one hold zeros (nothing ever adds to them) and
-                            // add nothing.  The 32-bit parts convert to fp64 exactly and so does their combination
-                            // (below 2^51), which is the integer sum itself.
-                            constexpr int MAXI = PB_MAX_BITS / LG;   // sets a lane can have
-                            constexpr int CH = LG == 4 ? 2 : 4;      // (a chunk covers eight sets, or four)
-                            static_assert(MAXI % CH == 0, "whole chunks");
-                            for (int k0 = 0; k0 * LG < nsets; k0 += CH, src += CH * LG * SET) {
-                                int4 t[CH][QN / 4];
-                                float sc[CH];
-#pragma unroll
-                                for (int c = 0; c < CH; ++c) {
-                                    const int i = lg + LG * (k0 + c);          // < PB_MAX_BITS
-#pragma unroll
-                                    for (int e = 0; e < QN / 4; ++e) t[c][e] = src[c * LG * SET + e];
-                                    // a merged pair carries the scale of its low bitlayer
-                                    sc[c] = s_scales[!merged ? i : min(2 * i + 1, m - 1)];
-                                }
-#pragma unroll
-                                for (int c = 0; c < CH; ++c)
-#pragma unroll
-                                    for (int e = 0; e < QN / 4; ++e) src[c * LG * SET + e] = make_int4(0, 0, 0, 0);
-#pragma unroll
-                                for (int c = 0; c < CH; ++c) {
-                                    double qd[QN];
+                        } else {
+                            // PK = 1, the quarters of one vector: digits 0, 2, 4, 6 in units of 1, digits 8 .. 14 in units
+                            // of 4^8, digits 1 .. 7 in units of 4, digits 9 .. 15 in units of 4^9; each below 2^31 in
+                            // magnitude (4369 * 9 * 32768 columns).  PK = 2, 4: even digits + 4 * odd digits of vector p.
+                            constexpr int SET = kTileRows * (QN / 4);   // int4s from one set of sums to the next
+                            if (v < NV && a.A) {
+                                for (int i = lg; i < nsets; i += LG, src += LG * SET) {
+                                    int qv[QN];
 #pragma unroll
                                     for (int e = 0; e < QN / 4; ++e) {
-                                        qd[4 * e] = (double)t[c][e].x; qd[4 * e + 1] = (double)t[c][e].y;
-                                        qd[4 * e + 2] = (double)t[c][e].z; qd[4 * e + 3] = (double)t[c][e].w;
+                                        const int4 t = src[e];
+                                        src[e] = make_int4(0, 0, 0, 0);
+                                        qv[4 * e] = t.x; qv[4 * e + 1] = t.y; qv[4 * e + 2] = t.z; qv[4 * e + 3] = t.w;
                                     }
 #pragma unroll
                                     for (int p = 0; p < PK; ++p) {
-                                        const double sum = PK == 1 ? fma(65536.0, fma(4.0, qd[3], qd[1]), fma(4.0, qd[2], qd[0]))
-                                                                   : fma(4.0, qd[PK + p], qd[p]);
-                                        z[p] = fma((double)sc[c], sum, z[p]);
+                                        const long long sum =
+                                            PK == 1 ? (long long)qv[0] + 4 * (long long)qv[2] +
+                                                          (((long long)qv[1] + 4 * (long long)qv[3]) << 16)
+                                                    : (long long)qv[p] + 4 * (long long)qv[PK + p];
+                                        const int n = n0 + v * PK + p;
+                                        if (row_ok && n < h.batch) a.A[((size_t)i * h.batch + n) * (size_t)a.R + row] = sum;
+                                    }
+                                }
+                            } else if (v < NV) {
+                                // The sets of a lane are read CH at a time, together with their scales, so that the LDS
+                                // latency is paid once: sets beyond the last one hold zeros (nothing ever adds to them) and
+                                // add nothing.  The 32-bit parts convert to fp64 exactly and so does their combination
+                                // (below 2^51), which is the integer sum itself.
+                                constexpr int MAXI = PB_MAX_BITS / LG;   // sets a lane can have
+                                constexpr int CH = LG == 4 ? 2 : 4;      // (a chunk covers eight sets, or four)
+                                static_assert(MAXI % CH == 0, "whole chunks");
+                                for (int k0 = 0; k0 * LG < nsets; k0 += CH, src += CH * LG * SET) {
+                                    int4 t[CH][QN / 4];
+                                    float sc[CH];
+#pragma unroll
+                                    for (int c = 0; c < CH; ++c) {
+                                        const int i = lg + LG * (k0 + c);          // < PB_MAX_BITS
+#pragma unroll
+                                        for (int e = 0; e < QN / 4; ++e) t[c][e] = src[c * LG * SET + e];
+                                        // a merged pair carries the scale of its low bitlayer
+                                        sc[c] = s_scales[!merged ? i : min(2 * i + 1, m - 1)];
+                                    }
+#pragma unroll
+                                    for (int c = 0; c < CH; ++c)
+#pragma unroll
+                                        for (int e = 0; e < QN / 4; ++e) src[c * LG * SET + e] = make_int4(0, 0, 0, 0);
+#pragma unroll
+                                    for (int c = 0; c < CH; ++c) {
+                                        double qd[QN];
+#pragma unroll
+                                        for (int e = 0; e < QN / 4; ++e) {
+                                            qd[4 * e] = (double)t[c][e].x; qd[4 * e + 1] = (double)t[c][e].y;
+                                            qd[4 * e + 2] = (double)t[c][e].z; qd[4 * e + 3] = (double)t[c][e].w;
+                                        }
+#pragma unroll
+                                        for (int p = 0; p < PK; ++p) {
+                                            const double sum = PK == 1 ? fma(65536.0, fma(4.0, qd[3], qd[1]), fma(4.0, qd[2], qd[0]))
+                                                                       : fma(4.0, qd[PK + p], qd[p]);
+                                            z[p] = fma((double)sc[c], sum, z[p]);
+                                        }
                                     }
                                 }
                             }

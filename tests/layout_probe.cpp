@@ -37,12 +37,13 @@ long long probe_workspace_bytes(unsigned layout, int rows, int cols, int bits, i
     return (long long)pb::workspace_bytes(L, batch);
 }
 
-// limits that the accumulator bounds depend on: {columns of a tiled matrix, columns with merged bitlayer pairs, column slices per row}
+// limits that the accumulator bounds depend on: {columns of a tiled matrix, columns with merged bitlayer pairs, column slices per row, bitlayer pairs that share accumulators}
 void probe_limits(int *out)
 {
     out[0] = pb::kMaxColsTile16;
     out[1] = pb::kMaxColsPairs;
     out[2] = pb::kMaxSlices;
+    out[3] = pb::kPairGroup;
 }
 
 }  // extern "C"

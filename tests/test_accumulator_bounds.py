@@ -2,7 +2,7 @@
 
 The kernel keeps the exact integer A_i[r] = sum_c bit_i[r, c] * x_q[c] of Algorithm 2 in narrower pieces: fp32
 accumulators of digit products per slice of columns, one 32-bit integer per lane, four 32-bit "quarter" sums per
-(row, bitlayer or pair) in LDS.  This test rebuilds those pieces in exact Python integers for the inputs that make
+(row, bitlayer or pair) in LDS; merged pairs add up in groups that share the accumulators, two 32-bit halves per lane.  This test rebuilds those pieces in exact Python integers for the inputs that make
 them largest (every weight digit at its maximum, every activation saturated) at the widest matrix the layout
 allows, and checks that each fits the type the kernel gives it and that they recombine to the exact sum.
 The limits come from csrc/pb_layout.h (compiled for the host); the digit arithmetic is restated here from
@@ -26,9 +26,9 @@ def limits(tmp_path_factory):
            "-o", str(out), os.path.join(ROOT, "tests", "layout_probe.cpp")]
     subprocess.check_call(cmd)
     L = ctypes.CDLL(str(out))
-    v = (ctypes.c_int * 3)()
+    v = (ctypes.c_int * 4)()
     L.probe_limits(v)
-    return {"cols": v[0], "cols_pairs": v[1], "slices": v[2]}
+    return {"cols": v[0], "cols_pairs": v[1], "slices": v[2], "pair_group": v[3]}
 
 
 def digits_of(xq):
@@ -88,6 +88,44 @@ def test_partial_sums_fit_at_the_widest_matrix(limits, pairs):
         signed = xq if xq < 2 ** 31 else xq - 2 ** 32
         eff = wd - 2 if sign_pair else wd
         assert total == eff * signed * cols
+        assert abs(total) < 2 ** 63
+
+
+@pytest.mark.parametrize("last_is_single", [False, True])
+def test_group_sums_fit_at_the_widest_matrix(limits, last_is_single):
+    """Merged pairs whose scales halve throughout share one set of accumulators: pair p of a group enters with the
+    factor 2^e, e = the distance between its low bitlayer and the group's last one (the block scale of the weight
+    operand).  Largest case: a full group, every weight digit 3, activations saturated; with an odd bits_used the
+    last unit of the last group is a single bitlayer (digit 0/1, factor 1, the pairs before it 2, 8, 32, ...)."""
+    cols, G = limits["cols_pairs"], limits["pair_group"]
+    slice_cols = limits["cols"] // limits["slices"]
+    if last_is_single:
+        factors = [2 ** (2 * (G - 1 - p) - 1) for p in range(G - 1)] + [1]
+        wdig = [3] * (G - 1) + [1]
+    else:
+        factors = [4 ** (G - 1 - p) for p in range(G)]
+        wdig = [3] * G
+    for xq, with_sign_pair in itertools.product(SATURATED, [False, True]):
+        d = digits_of(xq)
+        halves = []
+        for b in QUARTER_FIRST_DIGIT:
+            acc = [sum(f * w for f, w in zip(factors, wdig)) * d[b + 2 * c] * slice_cols for c in range(4)]
+            assert all(fits_fp32_exactly(a) for a in acc), (hex(xq & 0xFFFFFFFF), acc)
+            i0, i1 = acc[0] + 16 * acc[1], acc[2] + 16 * acc[3]       # converted register by register, as integers
+            assert fits_int32(i0) and fits_int32(i1)
+            if with_sign_pair:      # pair 0 of the group is the sign pair: minus 2 * sum_c x_q[c], times its factor
+                ones = [d[b + 2 * c] * slice_cols for c in range(4)]
+                s0, s1 = (ones[0] + 16 * ones[1]) * 2 * factors[0], (ones[2] + 16 * ones[3]) * 2 * factors[0]
+                assert fits_int32(s0) and fits_int32(s1)
+                i0, i1 = i0 - s0, i1 - s1
+                assert fits_int32(i0) and fits_int32(i1)
+            w0, w1 = i0 * cols // slice_cols, i1 * cols // slice_cols      # the LDS words: all slices of a row
+            assert fits_int32(w0) and fits_int32(w1), (hex(xq & 0xFFFFFFFF), b, w0, w1)
+            halves.append(w0 + 256 * w1)
+        total = halves[0] + 4 * halves[2] + ((halves[1] + 4 * halves[3]) << 16)
+        signed = xq if xq < 2 ** 31 else xq - 2 ** 32
+        eff = [w - 2 if (with_sign_pair and p == 0) else w for p, w in enumerate(wdig)]
+        assert total == sum(f * e for f, e in zip(factors, eff)) * signed * cols
         assert abs(total) < 2 ** 63
 
 

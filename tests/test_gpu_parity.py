@@ -89,7 +89,7 @@ def test_every_bit_width_and_prefix(pb, layout, bits):
 
 @pytest.mark.parametrize("bits", [2, 3, 5, 8])
 def test_scales_that_do_not_halve_are_applied_bitlayer_by_bitlayer(pb, bits):
-    """Any fp32 scales are legal input: the kernel merges bitlayer pairs only where scales[i] == 2 scales[i+1]."""
+    """Any fp32 scales are legal input: the kernel merges bitlayer pairs only if scales[i] == 2 scales[i+1] throughout."""
     W, X = synth.ragged(50, 1500, batch=3, case=40 + bits, xdist="normal")
     lin = pb.PackedLinear(dev(W), bits, max_batch=3)
     ref = oracle_reference(W, bits, X, bits)
@@ -107,6 +107,31 @@ def test_scales_that_do_not_halve_are_applied_bitlayer_by_bitlayer(pb, bits):
         Y_ref = (Y * 2.0 ** -16).astype(np.float32)
         print("bits", bits, kind, flush=True)
         assert_y_close(lin(dev(X), bits).cpu().numpy(), Y_ref, ref["A"], sc)
+
+
+@pytest.mark.parametrize("bits", [9, 10, 11, 12, 16])
+def test_pair_groups_share_accumulators(pb, bits):
+    """Batches with scales that halve throughout: up to five bitlayer pairs of a row tile add up in one set of
+    registers (pair p with the factor 4^(last - p), supplied by the block scale of the weight operand), further
+    pairs in a second group; prefixes on both sides of the group boundaries, with and without a last single bitlayer."""
+    for (R, C, N, case) in ((40, 1300, 3, 81), (17, 9000, 5, 82)):
+        W, X = synth.ragged(R, C, batch=N, case=case + bits, xdist="wide")
+        ms = sorted(m for m in {1, 2, 3, 9, 10, 11, 12, bits - 1, bits} if 1 <= m <= bits)
+        print("pair groups", bits, R, C, N, ms, flush=True)
+        run_layer(pb, W, bits, X, ms, layout=LAYOUTS["mfma"])
+
+
+@pytest.mark.parametrize("bits", [10, 11, 16])
+def test_pair_groups_at_their_limits(pb, bits):
+    """A full group of five pairs (and five pairs plus more) at 32768 columns, every weight digit at its maximum,
+    activations saturated: the shared accumulators and the 32-bit halves in LDS are as large as they get
+    (tests/test_accumulator_bounds.py works the bounds out on the host)."""
+    cols = 32768
+    X = limit_vectors(cols)
+    for name, W in limit_matrices(cols, bits):
+        print("pair groups at the limits", bits, name, flush=True)
+        run_layer(pb, W, bits, X, [9, 10, bits], layout=LAYOUTS["mfma"])
+        run_layer(pb, W, bits, X[:2], [10], layout=LAYOUTS["mfma"])
 
 
 @pytest.mark.parametrize("xdist", ["normal", "uniform", "relu", "wide"])
