@@ -692,6 +692,24 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
                         const bool row_ok = v < NV && row >= 0 && row < a.R;
                         int4 *src = reinterpret_cast<int4 *>(&abuf[pr & 1][v < NV ? v : 0][lg][jrow][0]);
+                        // bias and previous cell state of this lane's outputs: requested before the sums are read and
+                        // added up, so that their way through memory is not waited for at the end (range-checked
+                        // loads: 0 for absent arrays and for lanes without an output)
+                        constexpr int kNoOutput = 0x7FFFFFF0;   // an offset beyond every array
+                        const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+                            const_cast<float *>(a.bias), 0, a.bias ? a.R * 4 : 0, 0x00020000);
+                        const float bias_row =
+                            __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(rb, row_ok ? row * 4 : kNoOutput, 0, 0));
+                        const __amdgpu_buffer_rsrc_t rc = __builtin_amdgcn_make_buffer_rsrc(
+                            const_cast<float *>(a.c_prev), 0, a.c_prev ? h.batch * a.gate_h * 4 : 0, 0x00020000);
+                        float c_old[PK];
+#pragma unroll
+                        for (int p = 0; p < PK; ++p) {
+                            const int n = n0 + v * PK + p;
+                            const bool cell = row_ok && n < h.batch && (lane & 3) == 0 && lg == 0;
+                            c_old[p] = __uint_as_float(__builtin_amdgcn_raw_buffer_load_b32(
+                                rc, cell ? (n * a.gate_h + row) * 4 : kNoOutput, 0, 0));
+                        }
                         double z[PK];
 #pragma unroll
                         for (int p = 0; p < PK; ++p) z[p] = 0.0;
@@ -806,19 +824,25 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                 const int n = n0 + v * PK + p;
                                 const bool live = row_ok && n < h.batch;
                                 float y = (float)(z[p] * a.out_scale);
-                                if (a.bias && live) y += a.bias[row];
+                                if (a.bias && live) y += bias_row;
                                 if (a.c_prev) {
                                     // LSTM cell: the four lanes of a quad hold the gates i, f, g, o of one unit (row =
-                                    // unit for gate i); the first lane of the quad updates the unit
-                                    const float gi = __uint_as_float(dpp_mov<0x00>(__float_as_uint(y)));
-                                    const float gf = __uint_as_float(dpp_mov<0x55>(__float_as_uint(y)));
-                                    const float gg = __uint_as_float(dpp_mov<0xAA>(__float_as_uint(y)));
-                                    const float go = __uint_as_float(dpp_mov<0xFF>(__float_as_uint(y)));
+                                    // unit for gate i).  Every lane applies its own gate's nonlinearity (the logistic
+                                    // function as 0.5 tanh(y / 2) + 0.5: one evaluation per lane, side by side), then
+                                    // the first lane of the quad collects the four and updates the unit.
+                                    const bool is_g = (lane & 3) == 2;
+                                    const float th = tanhf(is_g ? y : 0.5f * y);
+                                    const float act = is_g ? th : fmaf(0.5f, th, 0.5f);
+                                    const float gi = __uint_as_float(dpp_mov<0x00>(__float_as_uint(act)));
+                                    const float gf = __uint_as_float(dpp_mov<0x55>(__float_as_uint(act)));
+                                    const float gg = __uint_as_float(dpp_mov<0xAA>(__float_as_uint(act)));
+                                    const float go = __uint_as_float(dpp_mov<0xFF>(__float_as_uint(act)));
+                                    const float cn = fmaf(gf, c_old[p], gi * gg);
+                                    const float hn = go * tanhf(cn);
                                     if ((lane & 3) == 0 && live && lg == 0) {
                                         const size_t at = (size_t)n * a.gate_h + (size_t)row;
-                                        const float cn = sigmoid_f(gf) * a.c_prev[at] + sigmoid_f(gi) * tanhf(gg);
                                         a.c_out[at] = cn;
-                                        a.h_out[at] = sigmoid_f(go) * tanhf(cn);
+                                        a.h_out[at] = hn;
                                     }
                                 } else {
                                     if (a.relu) y = fmaxf(y, 0.0f);
@@ -972,6 +996,9 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     a.pairs_out = (A && pairs_out) ? 1 : 0;
     a.bias = ep.bias; a.relu = ep.relu; a.c_prev = ep.c_prev; a.h_out = ep.h_out; a.c_out = ep.c_out;
     a.gate_h = L.gate_h;
+    // (the epilogue addresses the bias and the cell state with 32-bit byte offsets)
+    if (ep.bias && L.rows >= (1 << 29)) return (int)hipErrorInvalidValue;
+    if (ep.c_prev && (size_t)batch * (size_t)L.gate_h >= ((size_t)1 << 29)) return (int)hipErrorInvalidValue;
     h.packed_bytes = (uint32_t)packed_bytes(L);   // (the host API refuses matrices of 4 GiB and more)
     h.flags = (planes ? kPlanesGiven : 0u) | (X1 ? kSecondPart : 0u);
     h.layer_step = (uint32_t)(tile16_layer_stride(L) * 4);
