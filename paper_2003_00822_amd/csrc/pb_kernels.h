@@ -38,7 +38,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
                 int batch, float *Y, long long *A, bool pairs_out, const Epilogue &ep, hipStream_t st);
 
-// logistic function of the LSTM gates (one definition for the fused and the stand-alone cell update)
+// logistic function of the LSTM gates in the stand-alone cell update (the fused one evaluates 0.5 tanh(v / 2) + 0.5,
+// the same function, side by side with the tanh of the fourth gate)
 __device__ __forceinline__ float sigmoid_f(float v) { return 1.0f / (1.0f + expf(-v)); }
 
 // pb_lstm.hip: y = act(y + bias) in place, for the layout whose product kernel has no fused epilogue
