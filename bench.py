@@ -389,22 +389,23 @@ def same_gpu_references(torch, dev, W, X, per_m):
 
 
 def mfma_calibration(torch, pb, dev):
-    """The rate of the product kernel's FP4 matrix instruction on this GPU (pb_calib_mfma: constant operands, two
-    waves per SIMD on every compute unit): alone, with the expansion of one packed weight word per four
+    """The rate of the product kernel's FP4 matrix instruction on this GPU (the calibration loop of `paper_2003_00822_amd/csrc/calib`, a
+    library of its own beside the product: constant operands, two waves per SIMD on every compute unit): alone, with the expansion of one packed weight word per four
     instructions, and with the kernel's epilogue per chain of four.  On a SIMD the matrix and the vector-ALU
     instructions take turns, so the third figure is the ceiling of the batched regime with this much ALU work."""
+    from paper_2003_00822_amd import calib
     cus = torch.cuda.get_device_properties(dev).multi_processor_count
     buf = torch.empty(cus, dtype=torch.float32, device=dev)
     res = {}
     for mode, name in ((0, "instructions_alone"), (1, "with_weight_expansion"), (2, "with_expansion_and_epilogue")):
         ts = []
         for iters in (200, 2200):
-            pb.pb_calib_mfma(mode, iters, cus, buf)
+            calib.pb_calib_mfma(mode, iters, cus, buf)
             e0 = torch.cuda.Event(enable_timing=True)
             e1 = torch.cuda.Event(enable_timing=True)
             torch.cuda.synchronize()
             e0.record()
-            pb.pb_calib_mfma(mode, iters, cus, buf)
+            calib.pb_calib_mfma(mode, iters, cus, buf)
             e1.record()
             torch.cuda.synchronize()
             ts.append(e0.elapsed_time(e1) * 1e-3)

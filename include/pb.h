@@ -197,18 +197,6 @@ int pb_matmul_acc(const void *packed, const pb_desc *d, int bits_used, const flo
 int pb_matmul_acc_pairs(const void *packed, const pb_desc *d, int bits_used, const float *X, int batch, int64_t *A,
                         void *workspace, void *stream);
 
-/* Measurement aid, not a step of the method: a loop of the FP4 matrix
- * instruction of the product kernel on constant operands, `workgroups`
- * workgroups of 8 waves, 16 * iters instructions (65536 flop each) per wave.
- * mode 0: the instructions alone; 1: with the expansion of one packed weight
- * word per four instructions; 2: also with the kernel's epilogue (digit
- * weighting, conversion, LDS atomic) per chain of four.  The benchmark times it
- * to state what fraction of the matrix peak is reachable beside that ALU work.
- * out: [workgroups] fp32, written (a checksum that keeps the loop alive).
- * PB_EINVAL for mode outside 0..2, iters outside 1..2^20, workgroups outside
- * 1..65536 or a null pointer. */
-int pb_calib_mfma(int mode, int iters, int workgroups, float *out, void *stream);
-
 /* The two halves of pb_matmul, for callers that apply several weight matrices
  * to the same activations (or that time the halves separately):
  * pb_act_prep converts X to fixed point and writes its bit planes and plane

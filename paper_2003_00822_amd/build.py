@@ -1,8 +1,10 @@
-"""Build the HIP library of this package for gfx950, in-tree.
+"""Build the HIP libraries of this package for gfx950, in-tree.
 
 `python -m paper_2003_00822_amd.build` compiles `csrc/*.hip` into
 `paper_2003_00822_amd/libpbatch.so` with hipcc (cross-compiles without a GPU):
-one object per source, compiled in parallel, then one link.
+one object per source, compiled in parallel, then one link; and the calibration
+loop of the benchmark (`csrc/calib/`, not part of the product) into
+`paper_2003_00822_amd/libpbatch_calib.so`.
 """
 from __future__ import annotations
 
@@ -16,6 +18,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpbatch.so")
+CALIB_LIB = os.path.join(HERE, "libpbatch_calib.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
@@ -38,6 +41,10 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")))
 
 
+def calib_sources():
+    return sorted(glob.glob(os.path.join(CSRC, "calib", "*.hip")))
+
+
 def _compile(src: str, extra, verbose: bool) -> str:
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".%d.o" % os.getpid())
     cmd = [HIPCC] + FLAGS + FILE_FLAGS.get(os.path.basename(src), []) + list(extra) + ["-c", "-o", obj, src]
@@ -47,9 +54,9 @@ def _compile(src: str, extra, verbose: bool) -> str:
     return obj
 
 
-def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
+def build(verbose: bool = True, extra_flags=(), out: str = LIB, srcs=None) -> str:
     os.makedirs(OBJ_DIR, exist_ok=True)
-    srcs = sources()
+    srcs = sources() if srcs is None else srcs
     with ThreadPoolExecutor(max_workers=min(8, len(srcs))) as pool:
         objs = list(pool.map(lambda s: _compile(s, extra_flags, verbose), srcs))
     tmp = out + ".tmp.%d" % os.getpid()
@@ -66,7 +73,11 @@ def build(verbose: bool = True, extra_flags=(), out: str = LIB) -> str:
     return out
 
 
+def build_all(verbose: bool = True):
+    return [build(verbose), build(verbose, out=CALIB_LIB, srcs=calib_sources())]
+
+
 if __name__ == "__main__":
-    build()
-    print("built", LIB)
+    for lib in build_all():
+        print("built", lib)
     sys.exit(0)

@@ -1,12 +1,11 @@
-// Calibration loops for the roofline figures of the benchmark (not a step of the method): what rate the FP4
+// Calibration loops for the roofline figures of the benchmark (not a step of the method and not part of the
+// product library: built into a library of its own, which only bench.py and its test load): what rate the FP4
 // matrix instruction of the product kernel reaches on this chip by itself, and with the vector-ALU work that
 // the kernel does beside it (expansion of one packed weight word per step, digit weighting + conversion + LDS
 // atomic per chain of four steps).  The operands are constants; nothing is read from or written to memory but
 // one float per workgroup.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-#include "pb_kernels.h"
 
 namespace pb {
 
@@ -60,12 +59,20 @@ __global__ __launch_bounds__(512) void k_calib_mfma(int iters, float *out)
     if (threadIdx.x == 0) out[blockIdx.x] = s + (float)sums[0];
 }
 
-// One workgroup of 512 threads (two waves per SIMD) per compute unit; 16 * iters matrix instructions per wave.
-int launch_calib_mfma(int mode, int iters, int workgroups, float *out, hipStream_t st)
-{
-    void (*fn)(int, float *) = mode == 0 ? k_calib_mfma<0> : mode == 1 ? k_calib_mfma<1> : k_calib_mfma<2>;
-    hipLaunchKernelGGL(fn, dim3((unsigned)workgroups), dim3(512), 0, st, iters, out);
-    return (int)hipGetLastError();
-}
-
 }  // namespace pb
+
+// `workgroups` workgroups of 512 threads (two waves per SIMD), 16 * iters matrix instructions (65536 flop each) per
+// wave.  mode 0: the instructions alone; 1: with the expansion of one packed weight word per four instructions; 2:
+// also with an epilogue (digit weighting, conversion, LDS atomic) per chain of four.  out: [workgroups] fp32 on the
+// device, written (a checksum that keeps the loop alive).  Returns 0, 1 for arguments out of range (mode outside
+// 0..2, iters outside 1..2^20, workgroups outside 1..65536, a null pointer: nothing is launched), 2 if the launch failed.
+extern "C" int pb_calib_mfma(int mode, int iters, int workgroups, float *out, void *stream)
+{
+    if (mode < 0 || mode > 2 || iters < 1 || iters > (1 << 20) || workgroups < 1 || workgroups > 65536 || !out)
+        return 1;
+    void (*fn)(int, float *) = mode == 0   ? pb::k_calib_mfma<0>
+                               : mode == 1 ? pb::k_calib_mfma<1>
+                                           : pb::k_calib_mfma<2>;
+    hipLaunchKernelGGL(fn, dim3((unsigned)workgroups), dim3(512), 0, static_cast<hipStream_t>(stream), iters, out);
+    return hipGetLastError() == hipSuccess ? 0 : 2;
+}

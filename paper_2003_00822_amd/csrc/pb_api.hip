@@ -217,13 +217,6 @@ int pb_matmul_acc_pairs(const void *packed, const pb_desc *d, int bits_used, con
                          pb::Epilogue(), true);
 }
 
-int pb_calib_mfma(int mode, int iters, int workgroups, float *out, void *stream)
-{
-    if (mode < 0 || mode > 2 || iters < 1 || iters > (1 << 20) || workgroups < 1 || workgroups > 65536 || !out)
-        return PB_EINVAL;
-    return hip_status(pb::launch_calib_mfma(mode, iters, workgroups, out, static_cast<hipStream_t>(stream)));
-}
-
 int pb_act_prep(const pb_desc *d, const float *X, int batch, void *workspace, void *stream)
 {
     pb::Layout L;

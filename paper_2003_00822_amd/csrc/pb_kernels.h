@@ -44,7 +44,6 @@ __device__ __forceinline__ float sigmoid_f(float v) { return 1.0f / (1.0f + expf
 
 // pb_lstm.hip: y = act(y + bias) in place, for the layout whose product kernel has no fused epilogue
 int launch_bias_act(float *Y, const float *bias, int relu, int rows, int batch, hipStream_t st);
-int launch_calib_mfma(int mode, int iters, int workgroups, float *out, hipStream_t st);
 
 // pb_lstm.hip: gate nonlinearities and state update on the gate pre-activations.
 int launch_lstm_pointwise(const float *gates, const float *bias, const float *c_prev, int H, int batch, float *h_out,

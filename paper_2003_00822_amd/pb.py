@@ -27,7 +27,7 @@ PB_QUANT_SYMMETRIC, PB_QUANT_RANGE, PB_QUANT_SIGN, PB_QUANT_CLIP_SEARCH = 0, 1, 
 
 EXPORTS = [
     "pb_desc_init", "pb_desc_init_layout", "pb_quantize_pack_desc", "pb_quantize_pack_mode", "pb_packed_bytes", "pb_workspace_bytes", "pb_quantize_pack", "pb_unpack", "pb_matmul",
-    "pb_matmul_static", "pb_matmul_bias_act", "pb_matmul_acc", "pb_matmul_acc_pairs", "pb_calib_mfma", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
+    "pb_matmul_static", "pb_matmul_bias_act", "pb_matmul_acc", "pb_matmul_acc_pairs", "pb_act_prep", "pb_matmul_prepared", "pb_fixed_point", "pb_lstm_cell", "pb_strerror", "pb_last_hip_error",
 ]
 
 
@@ -83,8 +83,6 @@ def lib():
         L.pb_matmul_acc.restype = _I
         L.pb_matmul_acc_pairs.argtypes = [_P, _D, _I, _P, _I, _P, _P, _P]
         L.pb_matmul_acc_pairs.restype = _I
-        L.pb_calib_mfma.argtypes = [_I, _I, _I, _P, _P]
-        L.pb_calib_mfma.restype = _I
         L.pb_act_prep.argtypes = [_D, _P, _I, _P, _P]
         L.pb_act_prep.restype = _I
         L.pb_matmul_prepared.argtypes = [_P, _P, _D, _I, _I, _P, _P, _P]
@@ -210,11 +208,6 @@ def pb_matmul_acc(packed, d, bits_used, X, batch, A, workspace, stream=None):
     _check(lib().pb_matmul_acc(_ptr(packed, torch.uint8, "packed"), ctypes.byref(d), bits_used,
                                _ptr(X, torch.float32, "X"), batch, _ptr(A, torch.int64, "A"),
                                _ptr(workspace, torch.uint8, "workspace"), _stream(stream)), "pb_matmul_acc")
-
-
-def pb_calib_mfma(mode, iters, workgroups, out, stream=None):
-    _check(lib().pb_calib_mfma(mode, iters, workgroups, _ptr(out, torch.float32, "out"), _stream(stream)),
-           "pb_calib_mfma")
 
 
 def pb_matmul_acc_pairs(packed, d, bits_used, X, batch, A, workspace, stream=None):

@@ -618,14 +618,15 @@ def test_errors_surface_as_status(pb):
 
 
 def test_calibration_loop_runs_and_rejects_bad_arguments(pb):
+    from paper_2003_00822_amd import calib
     out = torch.zeros(4, dtype=torch.float32, device="cuda")
     for mode in (0, 1, 2):
-        pb.pb_calib_mfma(mode, 3, 4, out)
+        calib.pb_calib_mfma(mode, 3, 4, out)
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
     for bad in ((3, 1, 1), (0, 0, 1), (0, 1, 0)):
         with pytest.raises(Exception):
-            pb.pb_calib_mfma(bad[0], bad[1], bad[2], out)
+            calib.pb_calib_mfma(bad[0], bad[1], bad[2], out)
 
 
 def test_graph_replay_matches_eager(pb):
