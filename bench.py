@@ -42,8 +42,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--size", type=int, default=4096, help="FC layer is size x size (4096 = the headline config)")
     ap.add_argument("--bits", type=int, default=8, help="stored bitlayers B; bits_used sweeps 1..B")
-    ap.add_argument("--layout", choices=["mfma", "popc"], default="mfma",
-                    help="packed layout = kernel: matrix cores (default) or AND + popcount")
+    ap.add_argument("--layout", choices=["mfma", "popc", "pair"], default="mfma",
+                    help="packed layout = kernel: matrix cores (default), AND + popcount, or the matrix cores on the "
+                         "layout that stores the digits of the bitlayer pairs")
     ap.add_argument("--warm", action="store_true", help="reuse one weight copy (cache-resident) instead of the pool")
     ap.add_argument("--eager", action="store_true", help="plain launches from Python instead of HIP graph replay")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
@@ -94,8 +95,9 @@ def main():
     W, X = synth.fc_square(n, std, batch=1, cfg=2 if n == 4096 else 5)
     Wd = torch.from_numpy(W).to(dev)
     Xd = torch.from_numpy(X).to(dev)
-    mfma = args.layout == "mfma"
-    d = pb.pb_desc_init_layout(n, n, B, pb.PB_LAYOUT_TILE16_V1 if mfma else pb.PB_LAYOUT_ROWMAJOR_V1)
+    mfma = args.layout != "popc"
+    d = pb.pb_desc_init_layout(n, n, B, {"mfma": pb.PB_LAYOUT_TILE16_V1, "popc": pb.PB_LAYOUT_ROWMAJOR_V1,
+                                         "pair": pb.PB_LAYOUT_TILE16_PAIRS_V1}[args.layout])
     packed = pb.alloc_packed(d, dev)
     scales = torch.empty(max(B, 4), dtype=torch.float32, device=dev)
     pb.pb_quantize_pack_desc(Wd, d, packed, scales)
@@ -502,7 +504,7 @@ def size_sweep(torch, pb, dev, layout):
     rows = []
     gen = torch.Generator(device=dev)
     gen.manual_seed(200300822 + 6000)
-    lay = pb.PB_LAYOUT_TILE16_V1 if layout == "mfma" else pb.PB_LAYOUT_ROWMAJOR_V1
+    lay = {"mfma": pb.PB_LAYOUT_TILE16_V1, "popc": pb.PB_LAYOUT_ROWMAJOR_V1, "pair": pb.PB_LAYOUT_TILE16_PAIRS_V1}[layout]
     for n in (8192, 16384):
         B = 8
         Wd = torch.randn((n, n), device=dev, generator=gen) * 0.01
@@ -582,6 +584,7 @@ def batch_sweep(torch, pb, synth, dev):
         return best
 
     for name, lay, batches in (("mfma", pb.PB_LAYOUT_TILE16_V1, (1, 4, 16, 64, 256, 1024)),
+                               ("mfma, pairs layout", pb.PB_LAYOUT_TILE16_PAIRS_V1, (1, 4, 16, 64, 256, 1024)),
                                ("popc", pb.PB_LAYOUT_ROWMAJOR_V1, (1, 4, 16, 64, 256))):
         lin = pb.PackedLinear(Wd, B, max_batch=max(batches), layout=lay)
         for N in batches:
@@ -591,10 +594,10 @@ def batch_sweep(torch, pb, synth, dev):
             macs = float(n) * n * m * 32 * N
             row = {"kernel": name, "batch": N, "act_bits": 32, "us_per_call": round(t * 1e6, 1),
                    "us_per_vector": round(t * 1e6 / N, 2), "Tbitmac_per_s": round(macs / t / 1e12, 1)}
-            if name == "mfma":
+            if name.startswith("mfma"):
                 # matrix instructions issued: 16 digit rows (two planes each) per vector, and with more than one
-                # vector two bitlayers per instruction
-                units = m if N == 1 else (m + 1) // 2
+                # vector (on the pairs layout: always) two bitlayers per instruction
+                units = m if (N == 1 and name == "mfma") else (m + 1) // 2
                 row["mfma_issued_TFLOPs"] = round(2.0 * 16 * n * n * units * N / t / 1e12, 1)
                 row["mfma_frac"] = round(2.0 * 16 * n * n * units * N / t / 1e12 / FP4_PEAK_TFLOPS, 4)
             else:
@@ -607,16 +610,17 @@ def batch_sweep(torch, pb, synth, dev):
             rows.append(row)
         del lin
     # narrower activations on the matrix-core kernel (frac_bits as in table1_analog)
-    for (k, fb) in ((8, 4), (16, 12)):
-        lin = pb.PackedLinear(Wd, B, max_batch=64, frac_bits=fb, act_bits=k, layout=pb.PB_LAYOUT_TILE16_V1)
-        for N in (16, 64):
-            def f():
-                pb.pb_matmul(lin.packed, lin.scales, lin.desc, m, X[:N], N, Y[:N], lin.workspace)
-            t = time_calls(f, N)
-            rows.append({"kernel": "mfma", "batch": N, "act_bits": k, "us_per_call": round(t * 1e6, 1),
-                         "us_per_vector": round(t * 1e6 / N, 2),
-                         "Tbitmac_per_s": round(float(n) * n * m * k * N / t / 1e12, 1)})
-        del lin
+    for name, lay in (("mfma", pb.PB_LAYOUT_TILE16_V1), ("mfma, pairs layout", pb.PB_LAYOUT_TILE16_PAIRS_V1)):
+        for (k, fb) in ((8, 4), (16, 12)):
+            lin = pb.PackedLinear(Wd, B, max_batch=64, frac_bits=fb, act_bits=k, layout=lay)
+            for N in (16, 64):
+                def f():
+                    pb.pb_matmul(lin.packed, lin.scales, lin.desc, m, X[:N], N, Y[:N], lin.workspace)
+                t = time_calls(f, N)
+                rows.append({"kernel": name, "batch": N, "act_bits": k, "us_per_call": round(t * 1e6, 1),
+                             "us_per_vector": round(t * 1e6 / N, 2),
+                             "Tbitmac_per_s": round(float(n) * n * m * k * N / t / 1e12, 1)})
+            del lin
     return {"workload": "FC 8192x8192, B=8, bits_used=8, x~N(0,1), batch 1..1024, weights warm",
             "alu_peak_Gops": round(ALU_PEAK_GOPS, 1), "fp4_peak_TFLOPs": FP4_PEAK_TFLOPS, "rows": rows}
 
@@ -624,7 +628,7 @@ def batch_sweep(torch, pb, synth, dev):
 def batch_point(torch, pb, synth, dev, n, B, N, steps, layout):
     """One point of the batched regime by itself (cfg 5 recipe: W ~N(0, 0.01), x ~N(0, 1)), eager launches."""
     W, _ = synth.fc_square(n, 0.01, batch=1, cfg=5)
-    lay = pb.PB_LAYOUT_TILE16_V1 if layout == "mfma" else pb.PB_LAYOUT_ROWMAJOR_V1
+    lay = {"mfma": pb.PB_LAYOUT_TILE16_V1, "popc": pb.PB_LAYOUT_ROWMAJOR_V1, "pair": pb.PB_LAYOUT_TILE16_PAIRS_V1}[layout]
     lin = pb.PackedLinear(torch.from_numpy(W).to(dev), B, max_batch=N, layout=lay)
     gen = torch.Generator(device=dev)
     gen.manual_seed(200300822 + 5000)
@@ -641,11 +645,11 @@ def batch_point(torch, pb, synth, dev, n, B, N, steps, layout):
     e1.record()
     torch.cuda.synchronize()
     t = e0.elapsed_time(e1) * 1e-3 / steps
-    units = B if N == 1 else (B + 1) // 2
+    units = B if (N == 1 and layout == "mfma") else (B + 1) // 2
     return {"workload": "FC %dx%d, B=bits_used=%d, batch %d, x~N(0,1), weights warm, kernel %s" % (n, n, B, N, layout),
             "steps": steps, "us_per_call": round(t * 1e6, 1),
             "Tbitmac_per_s": round(float(n) * n * B * 32 * N / t / 1e12, 1),
-            "mfma_issued_TFLOPs": round(2.0 * 16 * n * n * units * N / t / 1e12, 1) if layout == "mfma" else None}
+            "mfma_issued_TFLOPs": round(2.0 * 16 * n * n * units * N / t / 1e12, 1) if layout != "popc" else None}
 
 
 def _host_threads():

@@ -63,6 +63,17 @@ typedef enum pb_status {
  *                       pb_lstm_cell runs as ONE launch.  Every other call works on it too and sees the
  *                       rows in their matrix order.  Chosen by the caller (pb_desc_init_layout). */
 #define PB_LAYOUT_TILE16_GATES_V1 0x50420003u
+/* PB_LAYOUT_TILE16_PAIRS_V1  the tiled layout for callers that serve batches: the bitlayers (2p, 2p + 1) are
+ *                       stored together as base-4 digits 2 w_(2p) + w_(2p+1), two bits per column (the digits
+ *                       of the even columns of a word in the block of bitlayer 2p, those of the odd columns in
+ *                       the block of bitlayer 2p + 1; bitlayer 0 enters complemented; an odd number of
+ *                       bitlayers is stored as the next even number, the last one paired with zeros, and
+ *                       pb_packed_bytes says so).  The matrix-core kernel then builds a weight operand of two
+ *                       bitlayers with six instead of ten operations: about 10 % faster from batch 16 on.
+ *                       Every call works on it (not pb_lstm_cell's single launch); with one vector it is slower than
+ *                       PB_LAYOUT_TILE16_V1, because an odd bits_used reads one bitlayer more.  Chosen by the
+ *                       caller (pb_desc_init_layout). */
+#define PB_LAYOUT_TILE16_PAIRS_V1 0x50420004u
 
 /* Shape and format of one packed weight matrix (host struct, plain data).
  * bits      B, the number of stored bitlayers = two's-complement width of the

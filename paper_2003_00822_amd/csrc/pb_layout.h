@@ -21,6 +21,13 @@
 //   packed row 16 t + 4 (u % 4) + gate = matrix row gate * H + u.  All four pre-activations of
 //   a hidden unit then end in one row tile, so the cell update can follow the product in
 //   the same launch.
+//
+// PB_LAYOUT_TILE16_PAIRS_V1: the same blocks, but the words of the bitlayers (2p, 2p + 1) hold base-4 digits
+//   d_c = 2 w_(2p)[c] + w_(2p+1)[c] instead of single bits: the word at the position of bitlayer 2p holds the digits of
+//   the even columns of its 32 columns (d_c in bits c, c + 1), the word at the position of bitlayer 2p + 1 those of the
+//   odd columns (d_c in bits c - 1, c).  Bitlayer 0 enters complemented (the digit 2 (1 - w_0) + w_1 of the sign
+//   pair, Section 3.2's sign bitlayer with the scale of its neighbour).  `stored_bits` = bits rounded up to an even
+//   number; a last single bitlayer is paired with zeros.
 #pragma once
 #include <stddef.h>
 #include <stdint.h>
@@ -50,6 +57,7 @@ constexpr int kPairGroup = 5;
 struct Layout {
     uint32_t layout;
     int rows, cols, bits;
+    int stored_bits;   // bitlayers that the packed buffer has room for (bits, or the next even number: pairs layout)
     int cw;        // words that hold real columns: ceil(cols / 32)
     int cwp;       // padded words per row
     int rows_p;    // padded rows
@@ -64,7 +72,11 @@ struct Layout {
     int gate_h;    // PB_LAYOUT_TILE16_GATES_V1: H = rows / 4 (rows are stored gate-interleaved), else 0
 };
 
-inline bool is_tile16(uint32_t layout) { return layout == PB_LAYOUT_TILE16_V1 || layout == PB_LAYOUT_TILE16_GATES_V1; }
+__host__ __device__ inline bool is_pairs(uint32_t layout) { return layout == PB_LAYOUT_TILE16_PAIRS_V1; }
+inline bool is_tile16(uint32_t layout)
+{
+    return layout == PB_LAYOUT_TILE16_V1 || layout == PB_LAYOUT_TILE16_GATES_V1 || is_pairs(layout);
+}
 
 // PB_LAYOUT_TILE16_GATES_V1: packed row of matrix row r, and back (-1 = a padding row).
 __host__ __device__ inline int gates_packed_row(int r, int H)
@@ -84,6 +96,7 @@ inline bool make_layout(uint32_t layout, int rows, int cols, int bits, Layout *L
     if (cols > PB_MAX_COLS) return false;
     L->layout = layout;
     L->rows = rows; L->cols = cols; L->bits = bits;
+    L->stored_bits = is_pairs(layout) ? (bits + 1) & ~1 : bits;
     L->cw = (cols + 31) / 32;
     L->ws = L->csplit = L->rpt = L->rt_count = L->cq = L->gate_h = 0;
     if (layout == PB_LAYOUT_ROWMAJOR_V1) {
@@ -137,7 +150,19 @@ __host__ __device__ inline size_t word_index(uint32_t layout, int cwp, size_t la
     return (size_t)layer * layer_words + (rt * cq + q) * 256 + in_block;
 }
 
-inline size_t packed_bytes(const Layout &L) { return L.layer_words * (size_t)L.bits * sizeof(uint32_t); }
+inline size_t packed_bytes(const Layout &L) { return L.layer_words * (size_t)L.stored_bits * sizeof(uint32_t); }
+
+// PB_LAYOUT_TILE16_PAIRS_V1: the two words (even columns, odd columns) of the digits 2 hi + lo of 32 columns, and back.
+__host__ __device__ inline void digits_of_pair(uint32_t hi, uint32_t lo, uint32_t *even, uint32_t *odd)
+{
+    *even = (lo & 0x55555555u) | ((hi << 1) & 0xAAAAAAAAu);
+    *odd = ((lo >> 1) & 0x55555555u) | (hi & 0xAAAAAAAAu);
+}
+__host__ __device__ inline void pair_of_digits(uint32_t even, uint32_t odd, uint32_t *hi, uint32_t *lo)
+{
+    *hi = ((even >> 1) & 0x55555555u) | (odd & 0xAAAAAAAAu);
+    *lo = (even & 0x55555555u) | ((odd << 1) & 0xAAAAAAAAu);
+}
 
 // Workspace: [meta: batch * kMetaInts int32][planes: batch * 32 * cwp uint32][gates: batch * rows fp32]
 inline size_t ws_meta_off(const Layout &, int) { return 0; }

@@ -262,7 +262,11 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c, i
 // PK: activation vectors per A operand.  With at most 16 (8) activation bits a vector has 8 (4) digits, the rest is
 // sign extension, so 2 (4) vectors share the sixteen rows of an operand and one instruction serves them all
 // (Section 3.1: fewer activation bits, less work).  NV then counts operands; a wave serves NV * PK vectors.
-template <int NQ, int NV, int MAXS, int RU, bool PAIR, int PK>
+// IL: the packed words hold the digits of the bitlayer pairs already (PB_LAYOUT_TILE16_PAIRS_V1: even columns of a word
+// in the block of the upper bitlayer, odd columns in the block of the lower one, sign bitlayer complemented): six
+// operations per word pair instead of ten and no complement; a unit always reads both blocks, and a last single
+// bitlayer is its pair's digit without the low bit.
+template <int NQ, int NV, int MAXS, int RU, bool PAIR, int PK, bool IL = false>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, const float *X0, uint32_t packed_bytes,
                                                     uint32_t flags, int cols0, int batch, uint32_t layer_step,
                                                     uint32_t round_step, int rounds_per_wg, int rt_count, int cq,
@@ -274,6 +278,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // (two units measured best: with three or four a call of 4096 or 8192 columns takes 0.2-0.5 us longer)
     constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
     static_assert(PK == 1 || PAIR, "packed vectors run on the pair kernels");
+    static_assert(!IL || PAIR, "the digit layout is read by the pair kernels");
     // sums per operand, bitlayer (or pair), row and kind of lane: the four operand rows of a lane of the result are
     // the even digits 0-6, the even digits 8-14, the odd digits 1-7, the odd digits 9-15 of one vector (PK = 1); the
     // even and the odd digits of two vectors (PK = 2: lanes kb = 0, 2 the first, kb = 1, 3 the second); with PK = 4 a
@@ -331,8 +336,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
         // past the last unit, and for chunks beyond the end of a ragged last slice, the descriptor has 0 records:
         // every lane is out of range, the load returns 0 and moves no data (no branch, so the compiler counts
         // the loads in flight exactly)
-        const int lo_layer = !PAIR ? ld_p : min(2 * ld_p + 1, m - 1);
-        const bool has_hi = PAIR && 2 * ld_p + 1 <= m - 1;
+        const int lo_layer = !PAIR ? ld_p : (IL ? 2 * ld_p + 1 : min(2 * ld_p + 1, m - 1));
+        const bool has_hi = PAIR && (IL || 2 * ld_p + 1 <= m - 1);
         const uint32_t lo_off = ld_round + (uint32_t)lo_layer * h.layer_step;
         const uint32_t hi_off = has_hi ? lo_off - h.layer_step : lo_off;
 #pragma unroll
@@ -581,14 +586,19 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // slices of a row at most 17 * 9 * 32768 * 341 = 1.71e9 < 2^31.
     // (With the sums of the pairs asked for, a group is one pair.)
     const int gsize = a.pairs_out ? 1 : kPairGroup;
-    auto low_layer = [&](int unit) { return min(2 * unit + 1, m - 1); };   // of a unit of a pair kernel
+    // low bitlayer of a unit of a pair kernel (IL: of the pair as stored, which a last single bitlayer has without
+    // using it: bitlayer m, with half the scale of bitlayer m - 1, minus half if that is the sign bitlayer)
+    auto low_layer = [&](int unit) { return IL ? 2 * unit + 1 : min(2 * unit + 1, m - 1); };
+    auto layer_scale = [&](int layer) {
+        return layer < m ? s_scales[layer] : (m == 1 ? -0.5f : 0.5f) * s_scales[m - 1];
+    };
     // sum_c x_q[c] over the slice, as this lane's share of it in the form of the group sums: the product with an
     // operand of digits 1, doubled (the digits of the sign pair stand 2 too high in every column) and with the
     // factor of pair 0 in its group
     int sxc[NV][2];
 #pragma unroll
     for (int v = 0; v < NV; ++v) sxc[v][0] = sxc[v][1] = 0;
-    if (PAIR && merged && m >= 2) {
+    if (PAIR && merged && (IL || m >= 2)) {
         const v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};
         const int e0 = low_layer(min(gsize, mp) - 1) - 1 + 1;   // (+ 1: doubled)
 #pragma unroll
@@ -624,8 +634,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
 #pragma unroll
         for (int k = 0; k < RU; ++k) {
             if (u0 + k < U) {
-                const int lo_layer = !PAIR ? pp : min(2 * pp + 1, m - 1);
-                const bool has_hi = PAIR && 2 * pp + 1 <= m - 1;
+                const int lo_layer = !PAIR ? pp : (IL ? 2 * pp + 1 : min(2 * pp + 1, m - 1));
+                const bool has_hi = PAIR && (IL || 2 * pp + 1 <= m - 1);
                 // (chunks beyond a ragged last slice, and the absent high bitlayer of a single unit, are zero words)
                 if (PAIR && merged) {
                     if (pp == gfirst) {
@@ -635,20 +645,30 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                     const int glast = min(gfirst + gsize, mp) - 1;             // last pair of this group
                     const int bscale = 128 + low_layer(glast) - lo_layer;     // 2^1 for the digits, 2^e for the pair
                     const bool sign_pair = pp == 0 && has_hi;
-                    const uint32_t inv = sign_pair ? 0xFFFFFFFFu : 0u;   // the sign bitlayer enters as 1 - w
+                    const uint32_t inv = (!IL && sign_pair) ? 0xFFFFFFFFu : 0u;   // the sign bitlayer enters as 1 - w
+                    // (IL) a last single bitlayer: the digits without their low bits
+                    const uint32_t dmask = (IL && 2 * pp + 1 >= m) ? 0x22222222u : 0x33333333u;
 #pragma unroll
                     for (int q = 0; q < NQ; ++q) {
-                        const u32x4 wl = ring[k][q], wh = ring[k][PAIR ? NQ + q : q] ^ inv;
+                        const u32x4 wl = ring[k][q];
+                        u32x4 wh = ring[k][PAIR ? NQ + q : q];
+                        if constexpr (!IL) wh ^= inv;
 #pragma unroll
                         for (int t = 0; t < 4; ++t) {
-                            const v8i b = weight_digit_operand(wh[t], wl[t]);
+                            v8i b;
+                            if constexpr (IL) {   // wh: digits of the even columns, wl: of the odd columns
+                                b = v8i{(int)(wh[t] & dmask), (int)(wl[t] & dmask), (int)((wh[t] >> 2) & dmask),
+                                        (int)((wl[t] >> 2) & dmask), 0, 0, 0, 0};
+                            } else {
+                                b = weight_digit_operand(wh[t], wl[t]);
+                            }
 #pragma unroll
                             for (int v = 0; v < NV; ++v)
                                 accg[v] = mfma_fp4(as_operand(pa[v][q][t]), b, accg[v], 128, bscale);
                         }
                     }
                     if (pp == glast) {
-                        finish_group(gfirst == 0 && m >= 2);
+                        finish_group(gfirst == 0 && (IL || m >= 2));
                         gfirst += gsize;
                         ++gset;
                     }
@@ -656,12 +676,22 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
 #pragma unroll
                     for (int h = PAIR ? 1 : 0; h >= 0; --h) {
                         if (h == 1 && !has_hi) continue;
+                        if (IL && h == 0 && 2 * pp + 1 >= m) continue;   // (the pair's lower bitlayer is not asked for)
                         v4f acc[NV];
 #pragma unroll
                         for (int v = 0; v < NV; ++v) acc[v] = v4f{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
                         for (int q = 0; q < NQ; ++q) {
-                            const u32x4 w = ring[k][h * NQ + q];
+                            u32x4 w = ring[k][h * NQ + q];
+                            if constexpr (IL) {   // the bits of one bitlayer out of the digit words
+                                const u32x4 ev = ring[k][NQ + q], od = ring[k][q];
+#pragma unroll
+                                for (int t = 0; t < 4; ++t) {
+                                    uint32_t upper, lower;
+                                    pair_of_digits(ev[t], od[t], &upper, &lower);
+                                    w[t] = h == 0 ? lower : (pp == 0 ? ~upper : upper);
+                                }
+                            }
 #pragma unroll
                             for (int t = 0; t < 4; ++t) {
                                 const v8i b = weight_operand(w[t]);
@@ -724,6 +754,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                 const int w[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
                                 // the group carries the scale of the low bitlayer of its last pair
                                 const int si = low_layer(min((g + 1) * gsize, mp) - 1);
+                                // (IL, sums of the pairs asked for) a single bitlayer came as twice itself, the sign
+                                // bitlayer by itself as -2 A_0
+                                const bool halve = IL && 2 * g + 1 >= m;
 #pragma unroll
                                 for (int p = 0; p < PK; ++p) {
                                     const int n = n0 + v * PK + p;
@@ -734,7 +767,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                         const long long sum = PK == 1   ? Q[0] + 4 * Q[2] + ((Q[1] + 4 * Q[3]) << 16)
                                                               : PK == 2 ? Q[p] + 4 * Q[2 + p]
                                                                         : (long long)w[p] + 4 * (long long)w[4 + p];
-                                        if (row_ok && n < h.batch) a.A[((size_t)g * h.batch + n) * (size_t)a.R + row] = sum;
+                                        if (row_ok && n < h.batch)
+                                            a.A[((size_t)g * h.batch + n) * (size_t)a.R + row] =
+                                                !halve ? sum : (g == 0 ? -sum : sum) / 2;
                                     } else {
                                         // (every part converts exactly; the last step rounds once if the sum is
                                         // beyond 2^53, as the conversion of the 64-bit integer would)
@@ -744,7 +779,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                         const double sum = PK == 1   ? fma(65536.0, fma(4.0, Q[3], Q[1]), fma(4.0, Q[2], Q[0]))
                                                            : PK == 2 ? fma(4.0, Q[2 + p], Q[p])
                                                                      : fma(4.0, (double)w[4 + p], (double)w[p]);
-                                        z[p] = fma((double)s_scales[si], sum, z[p]);
+                                        z[p] = fma((double)layer_scale(si), sum, z[p]);
                                     }
                                 }
                             }
@@ -860,24 +895,29 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
 }
 
 // The kernel variants: (chunks per wave, operands per wave, most slices per workgroup, ring depth in units), each for
-// single bitlayers, for pairs, and for pairs with two and four vectors per operand (fn[kind]; the variants with eight
-// operands have no kind 3: their sums would not fit the LDS).
+// single bitlayers, for pairs, for pairs with two and four vectors per operand, and the three pair kernels again for
+// the layout that stores the digits of the pairs (fn[kind]; the variants with eight operands have no kind with four
+// vectors per operand: their sums would not fit the LDS).
+constexpr int kKinds = 7;
 struct Variant {
     int nq, nv, maxs, ru;
-    const void *fn[4];
+    const void *fn[kKinds];
 };
-enum { kSingle = 0, kPairs = 1, kPairs2 = 2, kPairs4 = 3 };
-template <int NQ, int NV, int MAXS, int RU>
+enum { kSingle = 0, kPairs = 1, kPairs2 = 2, kPairs4 = 3, kDigits = 3 };   // kind of the digit layout = kDigits + pair kind
+template <int NQ, int NV, int MAXS, int RU, bool IL>
 static const void *pairs4_or_null()
 {
-    if constexpr (NV <= 4) return reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 4>);
+    if constexpr (NV <= 4) return reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 4, IL>);
     else return nullptr;
 }
-#define PB_VARIANT(NQ, NV, MAXS, RU)                                                           \
-    {NQ, NV, MAXS, RU, {reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false, 1>),    \
-                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 1>),     \
-                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 2>),     \
-                        pairs4_or_null<NQ, NV, MAXS, RU>()}}
+#define PB_VARIANT(NQ, NV, MAXS, RU)                                                                \
+    {NQ, NV, MAXS, RU, {reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false, 1>),         \
+                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 1>),          \
+                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 2>),          \
+                        pairs4_or_null<NQ, NV, MAXS, RU, false>(),                                  \
+                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 1, true>),    \
+                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 2, true>),    \
+                        pairs4_or_null<NQ, NV, MAXS, RU, true>()}}
 static const Variant kVariants[] = {
     PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
     PB_VARIANT(1, 2, 16, 1), PB_VARIANT(1, 2, 16, 2), PB_VARIANT(1, 2, 16, 4),
@@ -958,7 +998,7 @@ static size_t stage_bytes(int S) { return (size_t)S * kStageRows * sizeof(uint2)
 // is looked up once per kernel variant and workgroup size).
 static int resident_workgroups(int variant, int S, int kind)
 {
-    static int cache[4][kNumVariants][kMaxSlices + 1];
+    static int cache[kKinds][kNumVariants][kMaxSlices + 1];
     int *slot = &cache[kind][variant][S];
     int v = __atomic_load_n(slot, __ATOMIC_RELAXED);
     if (v > 0) return v;
@@ -1021,8 +1061,10 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     // asked for or the scales do not halve)
     bool pair = a.pairs_out || (!A && batch >= 2) || pk > 1;
     if (tuning().pair >= 0 && pk == 1) pair = a.pairs_out || (!A && tuning().pair != 0);
+    if (is_pairs(L.layout)) pair = true;   // (the digit layout is read by the pair kernels, whatever the call)
     if (L.cols > kMaxColsPairs) return (int)hipErrorInvalidValue;   // (cannot happen: pairs cover every width)
-    const int kind = !pair ? kSingle : (pk == 1 ? kPairs : (pk == 2 ? kPairs2 : kPairs4));
+    const int kind = !pair ? kSingle
+                           : (pk == 1 ? kPairs : (pk == 2 ? kPairs2 : kPairs4)) + (is_pairs(L.layout) ? kDigits : 0);
     int vi = pick_variant(L, slots, kind);
     if (vi < 0) return (int)hipErrorInvalidValue;
     const Variant &var = kVariants[vi];   // (the ring depth does not change a variant's occupancy: same registers +- a few)

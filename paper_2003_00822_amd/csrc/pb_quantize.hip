@@ -206,7 +206,21 @@ __global__ __launch_bounds__(256) void k_pack(const float *__restrict__ W, uint3
             lo = (lane == i) ? (uint32_t)bal : lo;
             hi = (lane == i) ? (uint32_t)(bal >> 32) : hi;
         }
-        if (lane < bits)
+        int stored = bits;
+        if (is_pairs(layout)) {
+            // lanes 2p, 2p + 1 hold the bitlayers of pair p (zeros beyond the last bitlayer); the even lane ends up
+            // with the digits of the even columns, the odd lane with those of the odd columns, for both words
+            stored = (bits + 1) & ~1;
+            if (lane == 0) { lo = ~lo; hi = ~hi; }      // the sign bitlayer enters as 1 - w
+            const uint32_t plo = (uint32_t)__shfl_xor((int)lo, 1, 64), phi = (uint32_t)__shfl_xor((int)hi, 1, 64);
+            const bool upper = !(lane & 1);              // this lane holds the upper bitlayer of its pair
+            uint32_t e0, o0, e1, o1;
+            digits_of_pair(upper ? lo : plo, upper ? plo : lo, &e0, &o0);   // columns 0-31 of the group
+            digits_of_pair(upper ? hi : phi, upper ? phi : hi, &e1, &o1);   // columns 32-63
+            lo = upper ? e0 : o0;
+            hi = upper ? e1 : o1;
+        }
+        if (lane < stored)
             *reinterpret_cast<uint2 *>(packed + word_index(layout, cwp, layer_words, lane, pr, 2 * g)) = make_uint2(lo, hi);
     }
 }
@@ -233,7 +247,15 @@ __global__ __launch_bounds__(256) void k_unpack(const uint32_t *__restrict__ pac
     uint32_t u = 0;
     const int pr = gate_h ? gates_packed_row(r, gate_h) : r;
     for (int i = 0; i < bits; ++i) {
-        uint32_t word = packed[word_index(layout, cwp, layer_words, i, pr, c >> 5)];
+        uint32_t word;
+        if (is_pairs(layout)) {
+            uint32_t upper, lower;
+            pair_of_digits(packed[word_index(layout, cwp, layer_words, i & ~1, pr, c >> 5)],
+                           packed[word_index(layout, cwp, layer_words, i | 1, pr, c >> 5)], &upper, &lower);
+            word = (i & 1) ? lower : (i == 0 ? ~upper : upper);
+        } else {
+            word = packed[word_index(layout, cwp, layer_words, i, pr, c >> 5)];
+        }
         u |= ((word >> (c & 31)) & 1u) << (bits - 1 - i);
     }
     int32_t v = (int32_t)(u << (32 - bits)) >> (32 - bits);  // sign-extend the B-bit code

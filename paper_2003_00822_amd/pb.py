@@ -22,6 +22,7 @@ PB_MAX_BATCH = 4096
 PB_LAYOUT_ROWMAJOR_V1 = 0x50420001   # AND + popcount kernel
 PB_LAYOUT_TILE16_V1 = 0x50420002     # matrix-core kernel (what pb_desc_init picks)
 PB_LAYOUT_TILE16_GATES_V1 = 0x50420003   # the same with the four gate rows of an LSTM unit in one row tile
+PB_LAYOUT_TILE16_PAIRS_V1 = 0x50420004   # the same with two bitlayers per word as base-4 digits (for serving batches)
 PB_ACT_NONE, PB_ACT_RELU = 0, 1
 PB_QUANT_SYMMETRIC, PB_QUANT_RANGE, PB_QUANT_SIGN, PB_QUANT_CLIP_SEARCH = 0, 1, 2, 3
 

@@ -46,4 +46,11 @@ void probe_limits(int *out)
     out[3] = pb::kPairGroup;
 }
 
+// PB_LAYOUT_TILE16_PAIRS_V1: the digit words of a bitlayer pair and back; out = {even, odd, upper, lower}
+void probe_pair_digits(unsigned upper, unsigned lower, unsigned *out)
+{
+    pb::digits_of_pair(upper, lower, &out[0], &out[1]);
+    pb::pair_of_digits(out[0], out[1], &out[2], &out[3]);
+}
+
 }  // extern "C"

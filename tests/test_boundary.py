@@ -129,6 +129,18 @@ def test_gate_interleaved_layout_sizes_and_checks(pb):
         pb.pb_desc_init_layout(10, 64, 4, gates)          # rows not a multiple of 4
 
 
+def test_pairs_layout_sizes(pb):
+    pairs = pb.PB_LAYOUT_TILE16_PAIRS_V1
+    d = pb.pb_desc_init_layout(100, 3000, 8, pairs)
+    assert d.layout == pairs and pb.pb_packed_bytes(d) == 8 * 112 * 96 * 4
+    # an odd number of bitlayers is stored as the next even number (the last one paired with zeros)
+    d = pb.pb_desc_init_layout(100, 3000, 5, pairs)
+    assert d.bits == 5 and pb.pb_packed_bytes(d) == 6 * 112 * 96 * 4
+    assert pb.pb_workspace_bytes(d, 3) == pb.pb_workspace_bytes(pb.pb_desc_init(100, 3000, 5), 3)
+    with pytest.raises(pb.PbError):
+        pb.pb_desc_init_layout(8, pb.PB_MAX_COLS + 1, 2, pairs)
+
+
 def test_bias_act_arguments_rejected_before_launch(pb):
     L = pb.lib()
     d = pb.pb_desc_init(64, 64, 4)

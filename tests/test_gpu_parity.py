@@ -20,8 +20,9 @@ def pb():
     return pbmod
 
 
-# every case runs on both packed layouts: the matrix-core kernel (default) and the AND + popcount kernel
-LAYOUTS = {"mfma": 0x50420002, "popc": 0x50420001}
+# every case runs on the packed layouts: the matrix-core kernel (default), the AND + popcount kernel, and the
+# matrix-core kernel on the layout that stores the digits of the bitlayer pairs
+LAYOUTS = {"mfma": 0x50420002, "popc": 0x50420001, "pair": 0x50420004}
 
 
 @pytest.fixture(params=sorted(LAYOUTS), scope="module")
@@ -87,11 +88,15 @@ def test_every_bit_width_and_prefix(pb, layout, bits):
     run_layer(pb, W, bits, X, list(range(1, bits + 1)), layout=layout)
 
 
+TILED = ["mfma", "pair"]    # the two layouts of the matrix-core kernel
+
+
+@pytest.mark.parametrize("lay", TILED)
 @pytest.mark.parametrize("bits", [2, 3, 5, 8])
-def test_scales_that_do_not_halve_are_applied_bitlayer_by_bitlayer(pb, bits):
+def test_scales_that_do_not_halve_are_applied_bitlayer_by_bitlayer(pb, bits, lay):
     """Any fp32 scales are legal input: the kernel merges bitlayer pairs only if scales[i] == 2 scales[i+1] throughout."""
     W, X = synth.ragged(50, 1500, batch=3, case=40 + bits, xdist="normal")
-    lin = pb.PackedLinear(dev(W), bits, max_batch=3)
+    lin = pb.PackedLinear(dev(W), bits, max_batch=3, layout=LAYOUTS[lay])
     ref = oracle_reference(W, bits, X, bits)
     rng = np.random.default_rng(bits)
     for kind in ("random", "one_off"):
@@ -109,8 +114,9 @@ def test_scales_that_do_not_halve_are_applied_bitlayer_by_bitlayer(pb, bits):
         assert_y_close(lin(dev(X), bits).cpu().numpy(), Y_ref, ref["A"], sc)
 
 
+@pytest.mark.parametrize("lay", TILED)
 @pytest.mark.parametrize("bits", [9, 10, 11, 12, 16])
-def test_pair_groups_share_accumulators(pb, bits):
+def test_pair_groups_share_accumulators(pb, bits, lay):
     """Batches with scales that halve throughout: up to five bitlayer pairs of a row tile add up in one set of
     registers (pair p with the factor 4^(last - p), supplied by the block scale of the weight operand), further
     pairs in a second group; prefixes on both sides of the group boundaries, with and without a last single bitlayer."""
@@ -118,11 +124,12 @@ def test_pair_groups_share_accumulators(pb, bits):
         W, X = synth.ragged(R, C, batch=N, case=case + bits, xdist="wide")
         ms = sorted(m for m in {1, 2, 3, 9, 10, 11, 12, bits - 1, bits} if 1 <= m <= bits)
         print("pair groups", bits, R, C, N, ms, flush=True)
-        run_layer(pb, W, bits, X, ms, layout=LAYOUTS["mfma"])
+        run_layer(pb, W, bits, X, ms, layout=LAYOUTS[lay])
 
 
+@pytest.mark.parametrize("lay", TILED)
 @pytest.mark.parametrize("bits", [10, 11, 16])
-def test_pair_groups_at_their_limits(pb, bits):
+def test_pair_groups_at_their_limits(pb, bits, lay):
     """A full group of five pairs (and five pairs plus more) at 32768 columns, every weight digit at its maximum,
     activations saturated: the shared accumulators and the 32-bit halves in LDS are as large as they get
     (tests/test_accumulator_bounds.py works the bounds out on the host)."""
@@ -130,8 +137,8 @@ def test_pair_groups_at_their_limits(pb, bits):
     X = limit_vectors(cols)
     for name, W in limit_matrices(cols, bits):
         print("pair groups at the limits", bits, name, flush=True)
-        run_layer(pb, W, bits, X, [9, 10, bits], layout=LAYOUTS["mfma"])
-        run_layer(pb, W, bits, X[:2], [10], layout=LAYOUTS["mfma"])
+        run_layer(pb, W, bits, X, [9, 10, bits], layout=LAYOUTS[lay])
+        run_layer(pb, W, bits, X[:2], [10], layout=LAYOUTS[lay])
 
 
 @pytest.mark.parametrize("xdist", ["normal", "uniform", "relu", "wide"])
@@ -297,8 +304,9 @@ def test_partial_sums_at_their_limits(pb, layout, cols):
             run_layer(pb, W, bits, X[n:n + 1], [2, 8], layout=layout)
 
 
+@pytest.mark.parametrize("lay", TILED)
 @pytest.mark.parametrize("fk", [(2, 4), (4, 8), (5, 9), (12, 16), (7, 12)])
-def test_vectors_that_share_an_operand(pb, fk):
+def test_vectors_that_share_an_operand(pb, fk, lay):
     """Activations of at most 16 (8) bits: two (four) vectors travel in one operand of the matrix-core kernel.
     Batches that fill the operands and that leave sub-vectors or whole operands empty, every route (per-bitlayer
     sums, pair sums, fp32 output), inputs that saturate at k bits."""
@@ -307,18 +315,19 @@ def test_vectors_that_share_an_operand(pb, fk):
                             (17, 9000, 9, 75), (40, 2100, 17, 76), (18, 700, 33, 77)):
         print("shared operands", fk, R, C, N, flush=True)
         W, X = synth.ragged(R, C, batch=N, case=case, xdist="wide" if case % 2 else "uniform")
-        run_layer(pb, W, 5, X, [1, 2, 5], frac_bits=f, act_bits=k, layout=LAYOUTS["mfma"])
+        run_layer(pb, W, 5, X, [1, 2, 5], frac_bits=f, act_bits=k, layout=LAYOUTS[lay])
 
 
+@pytest.mark.parametrize("lay", TILED)
 @pytest.mark.parametrize("k", [8, 16])
-def test_shared_operands_at_their_limits(pb, k):
+def test_shared_operands_at_their_limits(pb, k, lay):
     """All-ones / all-qmax bitlayers times activations saturated at k bits, 32768 columns, batches of 4 and 5."""
     cols, bits = 32768, 8
     X = limit_vectors(cols)                     # +-40000 saturate at +-2^(k-1) with frac_bits = k - 2
     for name, W in limit_matrices(cols, bits):
         print("shared operands at the limits", k, name, flush=True)
-        run_layer(pb, W, bits, X, [2, 7, 8], frac_bits=k - 2, act_bits=k, layout=LAYOUTS["mfma"])
-        run_layer(pb, W, bits, X[:4], [8], frac_bits=k - 2, act_bits=k, layout=LAYOUTS["mfma"])
+        run_layer(pb, W, bits, X, [2, 7, 8], frac_bits=k - 2, act_bits=k, layout=LAYOUTS[lay])
+        run_layer(pb, W, bits, X[:4], [8], frac_bits=k - 2, act_bits=k, layout=LAYOUTS[lay])
 
 
 def test_lstm_cell_with_narrow_activations_and_batch(pb):
@@ -514,7 +523,7 @@ def test_gate_layout_needs_rows_multiple_of_4(pb):
     assert e.value.status in (pb.PB_EINVAL, pb.PB_ESIZE)
 
 
-@pytest.mark.parametrize("lay", ["mfma", "popc"])
+@pytest.mark.parametrize("lay", ["mfma", "popc", "pair"])
 @pytest.mark.parametrize("act", [0, 1])
 def test_bias_and_relu_epilogue(pb, lay, act):
     W, X = synth.ragged(123, 900, batch=3, case=17, xdist="normal")
@@ -560,7 +569,8 @@ def test_lstm_fused_cell_small_ragged(pb):
         assert np.abs(c_out.cpu().numpy() - c_ref).max() < 2e-6, (H, I, N)
 
 
-@pytest.mark.parametrize("layout", [LAYOUTS["mfma"], LAYOUTS["popc"], GATES], ids=["mfma", "popc", "gates"])
+@pytest.mark.parametrize("layout", [LAYOUTS["mfma"], LAYOUTS["popc"], GATES, LAYOUTS["pair"]],
+                         ids=["mfma", "popc", "gates", "pair"])
 def test_lstm_cell_config4(pb, layout):
     """Config 4: 35 sequential LSTM steps.  Integer parity is checked per step with oracle-fed state
     (teacher forcing); the free-running GPU recurrence is compared to a tolerance."""

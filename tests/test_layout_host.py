@@ -52,6 +52,38 @@ def test_tiled_layout_sizes_and_padding(probe):
     assert layout_of(probe, TILE16, 0, 64, 1)["ok"] == 0
 
 
+PAIRS = 0x50420004
+
+
+def test_pairs_layout_sizes(probe):
+    """The layout with the digits of the bitlayer pairs has the blocks of the tiled layout and room for an even
+    number of bitlayers (a last single one is paired with zeros)."""
+    for bits, stored in ((1, 2), (2, 2), (3, 4), (8, 8), (15, 16), (16, 16)):
+        assert probe.probe_packed_bytes(PAIRS, 100, 3000, bits) == stored * 112 * 96 * 4
+        assert layout_of(probe, PAIRS, 100, 3000, bits) == layout_of(probe, TILE16, 100, 3000, bits)
+    assert probe.probe_workspace_bytes(PAIRS, 100, 3000, 3, 5) == probe.probe_workspace_bytes(TILE16, 100, 3000, 3, 5)
+
+
+def test_pair_digit_words(probe):
+    """Digit d_c = 2 upper_c + lower_c of column c: two bits at c, c + 1 of the even word (c even), at c - 1, c of
+    the odd word (c odd).  Worked by hand for a few patterns, then against the definition, and back."""
+    out = (ctypes.c_uint * 4)()
+    probe.probe_pair_digits(0b0110, 0b0011, out)       # columns 0..3: digits 1, 3, 2, 0
+    assert out[0] == (1 << 0) | (2 << 2)               # even columns 0, 2: digits 1 (bits 0-1), 2 (bits 2-3)
+    assert out[1] == (3 << 0) | (0 << 2)               # odd columns 1, 3: digits 3 (bits 0-1), 0 (bits 2-3)
+    assert (out[2], out[3]) == (0b0110, 0b0011)
+    import random
+    rng = random.Random(5)
+    for _ in range(200):
+        up, lo = rng.getrandbits(32), rng.getrandbits(32)
+        probe.probe_pair_digits(up, lo, out)
+        for c in range(32):
+            d = 2 * ((up >> c) & 1) + ((lo >> c) & 1)
+            word, pos = (out[0], c) if c % 2 == 0 else (out[1], c - 1)
+            assert (word >> pos) & 3 == d
+        assert (out[2], out[3]) == (up, lo)
+
+
 def test_gate_layout_sizes(probe):
     L = layout_of(probe, GATES, 4 * 38, 88, 5)
     assert L["gate_h"] == 38 and L["rt_count"] == 10 and L["rows_p"] == 160      # four units per tile
