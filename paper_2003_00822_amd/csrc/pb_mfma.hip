@@ -31,10 +31,12 @@
 // of two per instruction) supplies that factor, and up to five pairs of a row tile add up in the same registers.
 // The kernel checks scales[0] == -2 scales[1], scales[i] == 2 scales[i + 1] itself and multiplies bitlayer by
 // bitlayer when that does not hold (any other scales are legal input).
+// PB_LAYOUT_TILE16_PAIRS_V1 stores those digits instead of the bits (template flag IL below).
 //
 // Operands.  A (16 x 128) = 16 digit rows x 128 columns, B (128 x 16) = 128 columns x
 // 16 weight rows, D (16 x 16): lane l of D holds row j = l % 16 of the weights and
-// the digits 4 * (l / 16) + c in its four registers c, so the digit weighting is
+// the operand rows 4 * (l / 16) + c in its four registers c (rows 0-7 carry the even
+// digits, rows 8-15 the odd ones, see digit_of_row), so the digit weighting is
 // arithmetic inside a lane.  A lane's B operand is 32 columns of one weight row = ONE
 // packed word; register r, nibble n of both operands is column 4 n + r of the word:
 //     b0 = (w << 2) & 0x44444444   b1 = (w << 1) & 0x44444444
@@ -283,8 +285,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // the even digits 0-6, the even digits 8-14, the odd digits 1-7, the odd digits 9-15 of one vector (PK = 1); the
     // even and the odd digits of two vectors (PK = 2: lanes kb = 0, 2 the first, kb = 1, 3 the second); with PK = 4 a
     // lane holds two digits of each of two vectors and keeps two sums.  The 64 lanes of a wave add to different
-    // words.  Two buffers, used by alternate row tiles.
+    // words.  Two buffers, used by alternate row tiles.  (The group sums of merged pairs live in the same memory
+    // as [group][row][8 words] per buffer and operand: at most PB_MAX_BITS / 2 groups, which fits for every QN.)
     constexpr int QN = PK == 4 ? 8 : 4;
+    static_assert(PB_MAX_BITS * QN >= (PB_MAX_BITS / 2) * 8, "room for the group sums");
     __shared__ __align__(16) int abuf[2][NV][PB_MAX_BITS][kTileRows][QN];
     __shared__ float s_scales[PB_MAX_BITS];
     // staging area of the activation transpose, kStageRows rows of 8 bytes per wave (none when the planes are given)
