@@ -451,6 +451,25 @@ def test_config5_full_size_batch_64_sampled_rows(pb, layout):
         assert_y_close(Y_gpu[:, r], y, sub[:, :, 0], prep["scales"])
 
 
+@pytest.mark.parametrize("lay", TILED)
+def test_repeated_full_size_calls_are_bit_identical(pb, lay):
+    """All integer sums are exact, so a call's output does not depend on the schedule of its waves: the same call
+    repeated on the full grid (8192 x 8192, the launch configurations the benchmark times: one vector, a few
+    vectors, batch 64, and four vectors per operand) gives the same bits every time, whatever ran before it."""
+    torch.manual_seed(77)
+    n = 8192
+    W = torch.randn((n, n), device="cuda") * 0.01
+    X = torch.randn((64, n), device="cuda")
+    for (bits, act_bits, frac_bits) in ((8, 32, 16), (5, 8, 4)):
+        lin = pb.PackedLinear(W, bits, max_batch=64, frac_bits=frac_bits, act_bits=act_bits, layout=LAYOUTS[lay])
+        for N, m in ((1, bits), (1, 3), (5, bits), (64, bits), (64, bits - 1)):
+            first = lin(X[:N], m).clone()
+            for rep in range(6):
+                lin(X[(rep % 3):(rep % 3) + 1], 1 + rep % bits)      # other work in between
+                again = lin(X[:N], m)
+                assert torch.equal(first, again), (lay, bits, act_bits, N, m, rep)
+
+
 def test_extra_16384(pb, layout):
     W, X = synth.fc_square(16384, 0.01, cfg=6)
     bits = 2
