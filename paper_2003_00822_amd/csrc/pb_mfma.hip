@@ -908,20 +908,19 @@ struct Variant {
     const void *fn[kKinds];
 };
 enum { kSingle = 0, kPairs = 1, kPairs2 = 2, kPairs4 = 3, kDigits = 3 };   // kind of the digit layout = kDigits + pair kind
-template <int NQ, int NV, int MAXS, int RU, bool IL>
-static const void *pairs4_or_null()
+// (pair kernels exist with rings of one and two units, see pick_ring; with four vectors per operand for at most four
+// operands)
+template <int NQ, int NV, int MAXS, int RU, int PK, bool IL>
+static const void *pair_kernel()
 {
-    if constexpr (NV <= 4) return reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 4, IL>);
+    if constexpr (RU <= 2 && (PK < 4 || NV <= 4)) return reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, PK, IL>);
     else return nullptr;
 }
 #define PB_VARIANT(NQ, NV, MAXS, RU)                                                                \
     {NQ, NV, MAXS, RU, {reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, false, 1>),         \
-                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 1>),          \
-                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 2>),          \
-                        pairs4_or_null<NQ, NV, MAXS, RU, false>(),                                  \
-                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 1, true>),    \
-                        reinterpret_cast<const void *>(k_mfma<NQ, NV, MAXS, RU, true, 2, true>),    \
-                        pairs4_or_null<NQ, NV, MAXS, RU, true>()}}
+                        pair_kernel<NQ, NV, MAXS, RU, 1, false>(), pair_kernel<NQ, NV, MAXS, RU, 2, false>(),  \
+                        pair_kernel<NQ, NV, MAXS, RU, 4, false>(), pair_kernel<NQ, NV, MAXS, RU, 1, true>(),   \
+                        pair_kernel<NQ, NV, MAXS, RU, 2, true>(), pair_kernel<NQ, NV, MAXS, RU, 4, true>()}}
 static const Variant kVariants[] = {
     PB_VARIANT(1, 1, 16, 1), PB_VARIANT(1, 1, 16, 2), PB_VARIANT(1, 1, 16, 4),
     PB_VARIANT(1, 2, 16, 1), PB_VARIANT(1, 2, 16, 2), PB_VARIANT(1, 2, 16, 4),
@@ -981,15 +980,16 @@ static int pick_variant(const Layout &L, int batch, int kind)
 
 // The sibling of variant `vi` with the deepest ring that a wave with `units` units fills; with three units and
 // rings of 2 and 4 to choose from, the deeper one (a wave with one or two units is faster without empty ring slots,
-// one with three is 0.2 us faster when all three are in flight).
-static int pick_ring(int vi, int units)
+// one with three is 0.2 us faster when all three are in flight).  A unit of a pair kernel is two blocks per chunk:
+// two units in flight are its best (four measured 4-13 % slower at 8192 columns and 17-21 % at 4096).
+static int pick_ring(int vi, int units, int kind)
 {
     const int want = tuning().ru;
     int best = vi;
     for (int i = 0; i < kNumVariants; ++i) {
         const Variant &v = kVariants[i];
-        if (v.nq != kVariants[vi].nq || v.nv != kVariants[vi].nv || v.maxs != kVariants[vi].maxs) continue;
-        const int cap = units == 3 ? 4 : units;
+        if (v.nq != kVariants[vi].nq || v.nv != kVariants[vi].nv || v.maxs != kVariants[vi].maxs || !v.fn[kind]) continue;
+        const int cap = kind != kSingle ? (units < 2 ? units : 2) : (units == 3 ? 4 : units);
         if (want ? v.ru == want : (v.ru <= cap && v.ru > kVariants[best].ru)) best = i;
     }
     return best;
@@ -1015,7 +1015,8 @@ static int resident_workgroups(int variant, int S, int kind)
     if (stage_bytes(S) > 32 * 1024) {
         for (int i = 0; i < kNumVariants; ++i) {
             const Variant &o = kVariants[i];
-            if (o.nq != kVariants[variant].nq || o.nv != kVariants[variant].nv || o.maxs != kVariants[variant].maxs)
+            if (o.nq != kVariants[variant].nq || o.nv != kVariants[variant].nv || o.maxs != kVariants[variant].maxs ||
+                !o.fn[kind])
                 continue;
             if (hipFuncSetAttribute(o.fn[kind], hipFuncAttributeMaxDynamicSharedMemorySize,
                                     (int)stage_bytes(S)) != hipSuccess)
@@ -1076,7 +1077,7 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     const int groups = (slots + var.nv - 1) / var.nv;
     // Workgroups: as many as are resident at once (so that every wave builds its planes once and the weight
     // stream never waits for a second round of workgroups to start), each with whole row tiles.
-    int capacity = resident_workgroups(pick_ring(vi, 1 << 30), S, kind);   // of the sibling that needs the most registers
+    int capacity = resident_workgroups(pick_ring(vi, 1 << 30, kind), S, kind);   // of the sibling that needs the most registers
     if (capacity < 1) return (int)hipErrorInvalidValue;
     if (tuning().wgs > 0) capacity = tuning().wgs;
     int wgs = capacity / groups;
@@ -1086,7 +1087,7 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     wgs = (L.rt_count + h.rounds_per_wg - 1) / h.rounds_per_wg;
     void *args[] = {&h.packed, &h.X0, &h.packed_bytes, &h.flags, &h.cols0, &h.batch, &h.layer_step, &h.round_step,
                     &h.rounds_per_wg, &h.rt_count, &h.cq, &h.m, &a};
-    const Variant &run = kVariants[pick_ring(vi, h.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used))];
+    const Variant &run = kVariants[pick_ring(vi, h.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used), kind)];
     const hipError_t e = hipLaunchKernel(run.fn[kind], dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64),
                                          args, planes ? 0 : stage_bytes(S), st);
     return (int)(e != hipSuccess ? e : hipGetLastError());
