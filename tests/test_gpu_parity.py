@@ -148,7 +148,8 @@ def test_activation_distributions(pb, layout, xdist):
     run_layer(pb, W, 4, X, [1, 4], layout=layout)
 
 
-@pytest.mark.parametrize("shape_batch", [(40, 700, 5), (33, 4096, 7), (20, 5000, 3), (18, 8192, 6), (17, 9000, 2), (20, 17000, 3)])
+@pytest.mark.parametrize("shape_batch", [(40, 700, 5), (33, 4096, 7), (20, 5000, 3), (18, 8192, 6), (17, 9000, 2), (20, 17000, 3),
+                                         (25, 3000, 20), (19, 4096, 17), (21, 2000, 26)])
 def test_batches_that_do_not_fill_a_vector_group(pb, layout, shape_batch):
     R, C, N = shape_batch
     W, X = synth.ragged(R, C, batch=N, case=11, xdist="normal")
@@ -166,8 +167,8 @@ def test_maximum_batch(pb, layout):
 
 
 def test_random_configurations(pb):
-    """Seeded random shapes, widths, prefixes, batches, activation formats and distributions on the matrix-core
-    layout: codes, per-bitlayer sums, pair sums and outputs against the oracle."""
+    """Seeded random shapes, widths, prefixes, batches, activation formats and distributions on the layouts of the
+    matrix-core kernel: codes, per-bitlayer sums, pair sums and outputs against the oracle."""
     rng = np.random.default_rng(200300822)
     for case in range(120):
         R = int(rng.integers(1, 160))
@@ -179,7 +180,7 @@ def test_random_configurations(pb):
         xdist = ["normal", "uniform", "relu", "wide"][int(rng.integers(0, 4))]
         W, X = synth.ragged(R, C, batch=N, case=100 + case, xdist=xdist)
         print("case", case, (R, C, N), "bits", bits, "m", m, "act", act_bits, frac_bits, xdist, flush=True)
-        lay = GATES if (R % 4 == 0 and case % 3 == 0) else LAYOUTS["mfma"]
+        lay = GATES if (R % 4 == 0 and case % 3 == 0) else LAYOUTS["mfma" if case % 2 else "pair"]
         run_layer(pb, W, bits, X, m, frac_bits=frac_bits, act_bits=act_bits, layout=lay)
 
 
