@@ -572,6 +572,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     };
     const int j = lane & 15;
     int pp = 0, pr = 0;   // pair and round of the unit being multiplied
+    int turn = 0;         // (pr * RW) % nwaves, kept up by additions: the wave whose turn it is to finish a row tile
     // the end of a pass: the sums of this lane go to `set` in LDS
     auto finish = [&](const v4f (&acc)[NV], int set) {
 #pragma unroll
@@ -719,7 +720,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                     const int nsets = merged ? (mp + gsize - 1) / gsize : m;
                     constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per operand and row
                     constexpr int RW = (NV * LG * kTileRows + 63) / 64; // waves that one row tile's outputs occupy
-                    for (int duty = (wave + nwaves - (pr * RW) % nwaves) % nwaves; duty < RW; duty += nwaves) {
+                    for (int duty = wave - turn + (wave < turn ? nwaves : 0); duty < RW; duty += nwaves) {
                         const int slot = duty * 4 + (lane >> 4);
                         const int v = slot / LG, lg = slot % LG, jrow = lane & 15;
                         const int prow = (rt0 + pr) * kTileRows + jrow;
@@ -891,6 +892,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         }
                     }
                     ++pr;
+                    turn += RW;
+                    while (turn >= nwaves) turn -= nwaves;   // (RW <= 2: at most two rounds)
                 }
             }
             issue(ring[k]);
