@@ -452,6 +452,30 @@ def test_config5_full_size_batch_64_sampled_rows(pb, layout):
         assert_y_close(Y_gpu[:, r], y, sub[:, :, 0], prep["scales"])
 
 
+@pytest.mark.parametrize("bits", [1, 2, 5, 8])
+def test_pairs_layout_words(pb, bits):
+    """The stored words of PB_LAYOUT_TILE16_PAIRS_V1 against its definition, worked out in numpy from the words of the
+    default layout (same blocks, same positions): digit d_c = 2 upper_c + lower_c of the bitlayers (2p, 2p + 1), even
+    columns of a word in the block of bitlayer 2p (two bits at c), odd columns in the block of bitlayer 2p + 1 (two
+    bits at c - 1); bitlayer 0 complemented; a last single bitlayer paired with zeros."""
+    W, _ = synth.ragged(37, 1100, batch=1, case=300 + bits)
+    plain = pb.PackedLinear(dev(W), bits)
+    pairs = pb.PackedLinear(dev(W), bits, layout=LAYOUTS["pair"])
+    stored = (bits + 1) & ~1
+    a = plain.packed.cpu().numpy().view(np.uint32).reshape(bits, -1)
+    b = pairs.packed.cpu().numpy().view(np.uint32).reshape(stored, -1)
+    assert pairs.packed.numel() == stored * a.shape[1] * 4
+    for p in range(stored // 2):
+        upper = a[2 * p].copy()
+        if p == 0:
+            upper = ~upper
+        lower = a[2 * p + 1] if 2 * p + 1 < bits else np.zeros_like(upper)
+        even = (lower & np.uint32(0x55555555)) | ((upper << np.uint32(1)) & np.uint32(0xAAAAAAAA))
+        odd = ((lower >> np.uint32(1)) & np.uint32(0x55555555)) | (upper & np.uint32(0xAAAAAAAA))
+        assert (b[2 * p] == even).all(), (bits, p, "even columns")
+        assert (b[2 * p + 1] == odd).all(), (bits, p, "odd columns")
+
+
 @pytest.mark.parametrize("lay", TILED)
 def test_repeated_full_size_calls_are_bit_identical(pb, lay):
     """All integer sums are exact, so a call's output does not depend on the schedule of its waves: the same call
