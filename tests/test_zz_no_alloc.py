@@ -1,6 +1,6 @@
 """The entry point that allocates nothing (pb_matmul_static: the workspace lives in a device array of the library)
 against pb_matmul, through the C ABI: same kernels, so the outputs must be identical bit for bit; two calls in a
-row, the second with a smaller input, on the layout whose kernels use the workspace and on the default one."""
+row, the second with a smaller input, on the layout whose kernels use the workspace and on the two tiled ones."""
 import ctypes
 
 import numpy as np
@@ -36,9 +36,10 @@ def raw_static(pb, lin, X, m, Y):
     return rc
 
 
-@pytest.mark.parametrize("layout_name", ["popc", "mfma"])
+@pytest.mark.parametrize("layout_name", ["popc", "mfma", "pair"])
 def test_static_scratch_matches_pb_matmul_twice(pb, layout_name):
-    layout = {"popc": pb.PB_LAYOUT_ROWMAJOR_V1, "mfma": pb.PB_LAYOUT_TILE16_V1}[layout_name]
+    layout = {"popc": pb.PB_LAYOUT_ROWMAJOR_V1, "mfma": pb.PB_LAYOUT_TILE16_V1,
+              "pair": pb.PB_LAYOUT_TILE16_PAIRS_V1}[layout_name]
     bits = 6
     # first call: 300 x 2100, batch 5; second call: a smaller matrix and batch (the scratch keeps the first call's planes)
     for (R, C, N, m, case) in ((300, 2100, 5, 6, 61), (70, 500, 2, 3, 62)):
