@@ -200,6 +200,9 @@ __device__ __forceinline__ uint2 lds_read_transposed(const uint2 *row)
 // register are contiguous; a word takes 320 bytes, so that the 64-byte pieces that the lanes of a write put into
 // adjacent words fall into different banks, and every position of a lane is a constant away from its first.
 constexpr int kStageRows = 16 * 40;
+// LDS integers of the kernels that cover wide rows in several passes (96 KB: with the staging areas of eight waves a
+// workgroup stays below the 160 KB of a compute unit)
+constexpr int kSplitInts = 24576;
 __device__ __forceinline__ int stage_row(int w, int r, int n) { return w * 40 + 8 * r + n; }
 
 // The same operand from the two plane words (bit c = column c) of a digit row: p0 the lower plane, p1 the upper
@@ -268,7 +271,12 @@ __device__ __forceinline__ v4f mfma_fp4(const v8i a, const v8i b, const v4f c, i
 // in the block of the upper bitlayer, odd columns in the block of the lower one, sign bitlayer complemented): six
 // operations per word pair instead of ten and no complement; a unit always reads both blocks, and a last single
 // bitlayer is its pair's digit without the low bit.
-template <int NQ, int NV, int MAXS, int RU, bool PAIR, int PK, bool IL = false>
+// SPLIT: the columns of a row are covered in several passes, each with the waves' digit rows of its own range of
+// MAXS * NQ chunks at most, over the same row tiles; a row tile's sums stay in LDS (one buffer per row tile of the
+// round, as many row tiles per round as fit) and the last pass finishes it.  For batches on rows wider than the
+// registers of a workgroup hold digit rows of four operands for: each expanded weight word then still serves four
+// operands, at the price of rebuilding the digit rows once per pass and round.
+template <int NQ, int NV, int MAXS, int RU, bool PAIR, int PK, bool IL = false, bool SPLIT = false>
 __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, const float *X0, uint32_t packed_bytes,
                                                     uint32_t flags, int cols0, int batch, uint32_t layer_step,
                                                     uint32_t round_step, int rounds_per_wg, int rt_count, int cq,
@@ -281,6 +289,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     constexpr int PRE = NQ >= 4 ? 1 : (RU < 2 ? RU : 2);
     static_assert(PK == 1 || PAIR, "packed vectors run on the pair kernels");
     static_assert(!IL || PAIR, "the digit layout is read by the pair kernels");
+    static_assert(!SPLIT || PAIR, "the kernels that split the columns are pair kernels");
     // sums per operand, bitlayer (or pair), row and kind of lane: the four operand rows of a lane of the result are
     // the even digits 0-6, the even digits 8-14, the odd digits 1-7, the odd digits 9-15 of one vector (PK = 1); the
     // even and the odd digits of two vectors (PK = 2: lanes kb = 0, 2 the first, kb = 1, 3 the second); with PK = 4 a
@@ -289,23 +298,35 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // as [group][row][8 words] per buffer and operand: at most PB_MAX_BITS / 2 groups, which fits for every QN.)
     constexpr int QN = PK == 4 ? 8 : 4;
     static_assert(PB_MAX_BITS * QN >= (PB_MAX_BITS / 2) * 8, "room for the group sums");
-    __shared__ __align__(16) int abuf[2][NV][PB_MAX_BITS][kTileRows][QN];
+    // (SPLIT: one buffer per row tile of a pass, see below, in `sbuf`)
+    __shared__ __align__(16) int abuf[SPLIT ? 1 : 2][SPLIT ? 1 : NV][SPLIT ? 1 : PB_MAX_BITS][kTileRows][QN];
+    __shared__ __align__(16) int sbuf[SPLIT ? kSplitInts : 4];
     __shared__ float s_scales[PB_MAX_BITS];
     // staging area of the activation transpose, kStageRows rows of 8 bytes per wave (none when the planes are given)
     extern __shared__ __align__(16) unsigned char stage_lds[];
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int nwaves = (h.cq + NQ - 1) / NQ;                    // = blockDim.x / 64 (the launcher's S), from a preloaded argument
+    // SPLIT: `parts` passes over the columns, each of cq_part chunks (every wave has the same slice in every pass,
+    // a wave of the last pass maybe none); the loop below runs pass after pass, round after round.
+    const int parts = SPLIT ? (h.cq + MAXS * NQ - 1) / (MAXS * NQ) : 1;
+    const int cq_part = SPLIT ? (h.cq + parts - 1) / parts : h.cq;   // chunks per pass
+    const int nwaves = (cq_part + NQ - 1) / NQ;                 // = blockDim.x / 64 (the launcher's S), from a preloaded argument
     const int n0 = blockIdx.y * NV * PK;                        // first activation vector of this workgroup
     const int m = h.m;
-    const int q0 = wave * NQ;                                   // first chunk of this wave's column slice
-    const int nq = min(NQ, h.cq - q0);                          // chunks it really has (>= 1 by construction)
-    const int rt0 = blockIdx.x * h.rounds_per_wg;
-    const int rounds = min(h.rounds_per_wg, h.rt_count - rt0);  // >= 1 by construction
+    const int rt_first = blockIdx.x * h.rounds_per_wg;
+    const int rounds_all = min(h.rounds_per_wg, h.rt_count - rt_first);  // >= 1 by construction
     // units of a row tile: the pairs (0, 1), (2, 3), ..., and a last single bitlayer if m is odd
     const int mp = PAIR ? (m + 1) / 2 : m;
-    const int U = rounds * mp;
+    int turn = 0;         // (row tiles finished * RW) % nwaves, kept up by additions: the wave whose turn it is to finish a row tile
+  for (int rt_base = 0, part = 0;;) {
+    const int q0 = (part * nwaves + wave) * NQ;                 // first chunk of this wave's column slice
+    const int nq = min(NQ, h.cq - q0);                          // chunks it really has (>= 1 by construction; SPLIT: maybe none)
+    const int rt0 = rt_first + rt_base;
+    // (SPLIT: row tiles of this pass: until the scales are known, a number that has room in either case; the first
+    // requests of the ring, all that happens until then, do not depend on which)
+    int rounds = SPLIT ? min(rounds_all - rt_base, kSplitInts / (NV * PB_MAX_BITS * kTileRows * QN)) : rounds_all;
+    int U = rounds * mp;
 
     // layer scales, lane i holds scales[i] (and the next one, for the check of the pairs): requested after the
     // first weights (nothing that a wave requests before them may depend on the argument structure, which is still
@@ -367,8 +388,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // and before any wave requests weights: the memory pipeline of a CU returns data in request order, so an
     // activation load queued behind another wave's weight loads (HBM misses) would arrive a memory latency late.
     auto zero_sums_and_meet = [&]() {
-        for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * QN * kTileRows; i += nwaves * 64)
-            (&abuf[0][0][0][0][0])[i] = 0;
+        if constexpr (SPLIT) {
+            // (later passes find the sums of the passes before them, or the zeros that the final sums left)
+            if (rt_base == 0 && part == 0)
+                for (int i = threadIdx.x; i < kSplitInts; i += nwaves * 64) sbuf[i] = 0;
+        } else {
+            for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * QN * kTileRows; i += nwaves * 64)
+                (&abuf[0][0][0][0][0])[i] = 0;
+        }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
         __builtin_amdgcn_sched_barrier(0);
@@ -549,6 +576,18 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
         const bool off = lane + 1 < m && !(scv == (lane == 0 ? -2.0f : 2.0f) * scn);
         merged = __builtin_amdgcn_ballot_w64(off) == 0;
     }
+    // (With the sums of the pairs asked for, a group is one pair.)
+    const int gsize = a.pairs_out ? 1 : kPairGroup;
+    const int nsets = merged ? (mp + gsize - 1) / gsize : m;   // sets of sums of a row tile and operand
+    // SPLIT: the sums of a row tile are NV * set_ints integers, row tile after row tile (group sums take 8 integers
+    // per row; bitlayer by bitlayer every operand has room for all PB_MAX_BITS sets, which the final sum may read)
+    const int set_ints = merged ? nsets * (kTileRows * 8) : PB_MAX_BITS * kTileRows * QN;
+    if constexpr (SPLIT) {
+        const int left = rounds_all - rt_base, cap = kSplitInts / (NV * set_ints);
+        const int passes = (left + cap - 1) / cap;
+        rounds = (left + passes - 1) / passes;   // (even shares)
+        U = rounds * mp;
+    }
     __builtin_amdgcn_sched_barrier(0);   // the rest of the ring is requested after the activations have arrived
 #pragma unroll
     for (int k = PRE; k < RU; ++k) issue(ring[k]);
@@ -572,15 +611,20 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     };
     const int j = lane & 15;
     int pp = 0, pr = 0;   // pair and round of the unit being multiplied
-    int turn = 0;         // (pr * RW) % nwaves, kept up by additions: the wave whose turn it is to finish a row tile
-    // the end of a pass: the sums of this lane go to `set` in LDS
+    // the sums of operand v of the row tile being multiplied: two buffers used by alternate row tiles, or (SPLIT)
+    // one per row tile of the pass
+    auto sums_of = [&](int v) -> int * {
+        if constexpr (SPLIT) return sbuf + (pr * NV + v) * set_ints;
+        else return &abuf[pr & 1][v][0][0][0];
+    };
+    // the end of a bitlayer: the sums of this lane go to `set` in LDS
     auto finish = [&](const v4f (&acc)[NV], int set) {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
             int ls[LS];
             lane_sums(acc[v], ls);
 #pragma unroll
-            for (int e = 0; e < LS; ++e) atomicAdd(&abuf[pr & 1][v][set][j][LS * kb + e], ls[e]);
+            for (int e = 0; e < LS; ++e) atomicAdd(sums_of(v) + (set * kTileRows + j) * QN + LS * kb + e, ls[e]);
         }
     };
     // Merged pairs: the pairs of a row tile accumulate in ONE set of registers.  With all scales halving, pair p
@@ -589,8 +633,6 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     // update instead of one per pair.  Bounds: a register holds at most 9 * 2048 * (1 + 4 + .. + 4^4) = 6.3 M < 2^24
     // (exact in fp32); the two halves c0 + 16 c1 and c2 + 16 c3 of a lane are integers of their own in LDS, over the
     // slices of a row at most 17 * 9 * 32768 * 341 = 1.71e9 < 2^31.
-    // (With the sums of the pairs asked for, a group is one pair.)
-    const int gsize = a.pairs_out ? 1 : kPairGroup;
     // low bitlayer of a unit of a pair kernel (IL: of the pair as stored, which a last single bitlayer has without
     // using it: bitlayer m, with half the scale of bitlayer m - 1, minus half if that is the sign bitlayer)
     auto low_layer = [&](int unit) { return IL ? 2 * unit + 1 : min(2 * unit + 1, m - 1); };
@@ -630,7 +672,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                 i0 -= sxc[v][0];
                 i1 -= sxc[v][1];
             }
-            int *dst = &abuf[pr & 1][v][0][0][0] + gset * (kTileRows * 8) + j * 8 + 2 * kb;
+            int *dst = sums_of(v) + gset * (kTileRows * 8) + j * 8 + 2 * kb;
             atomicAdd(dst, i0);
             atomicAdd(dst + 1, i1);
         }
@@ -717,16 +759,17 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                     pp = 0;
                     gfirst = gset = 0;
                     __syncthreads();
-                    const int nsets = merged ? (mp + gsize - 1) / gsize : m;
                     constexpr int LG = NV >= 4 ? 1 : 4 / NV;            // lanes per operand and row
                     constexpr int RW = (NV * LG * kTileRows + 63) / 64; // waves that one row tile's outputs occupy
-                    for (int duty = wave - turn + (wave < turn ? nwaves : 0); duty < RW; duty += nwaves) {
+                    // (SPLIT: only the last pass over the columns finishes the row tiles)
+                    for (int duty = (SPLIT && part + 1 < parts) ? RW : wave - turn + (wave < turn ? nwaves : 0); duty < RW;
+                         duty += nwaves) {
                         const int slot = duty * 4 + (lane >> 4);
                         const int v = slot / LG, lg = slot % LG, jrow = lane & 15;
                         const int prow = (rt0 + pr) * kTileRows + jrow;
                         const int row = a.gate_h ? gates_matrix_row(prow, a.gate_h) : prow;
                         const bool row_ok = v < NV && row >= 0 && row < a.R;
-                        int4 *src = reinterpret_cast<int4 *>(&abuf[pr & 1][v < NV ? v : 0][lg][jrow][0]);
+                        int4 *src = reinterpret_cast<int4 *>(sums_of(v < NV ? v : 0) + (lg * kTileRows + jrow) * QN);
                         // bias and previous cell state of this lane's outputs: requested before the sums are read and
                         // added up, so that their way through memory is not waited for at the end (range-checked
                         // loads: 0 for absent arrays and for lanes without an output)
@@ -751,7 +794,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         if (PAIR && merged) {
                             // group sums: the halves (i0, i1) of the four kinds of lanes; Q_kb = i0 + 256 i1 is what a
                             // lane of kind kb would have had in one word
-                            int *grp = &abuf[pr & 1][v < NV ? v : 0][0][0][0] + jrow * 8;
+                            int *grp = sums_of(v < NV ? v : 0) + jrow * 8;
                             for (int g = lg; v < NV && g < nsets; g += LG) {
                                 int4 *g4 = reinterpret_cast<int4 *>(grp + g * (kTileRows * 8));
                                 const int4 t0 = g4[0], t1 = g4[1];
@@ -899,6 +942,13 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
             issue(ring[k]);
         }
     }
+    if constexpr (!SPLIT) break;
+    if (++part == parts) {
+        part = 0;
+        rt_base += rounds;
+        if (rt_base >= rounds_all) break;
+    }
+  }
 }
 
 // The kernel variants: (chunks per wave, operands per wave, most slices per workgroup, ring depth in units), each for
@@ -938,17 +988,24 @@ static const Variant kVariants[] = {
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
+// The kernels that cover rows of more than 8192 columns in several passes (two chunks and four operands per wave,
+// eight waves, two units in flight), by kind: pair kernels only.
+constexpr int kSplitNQ = 2, kSplitNV = 4, kSplitMaxS = 8;
+#define PB_SPLIT(PK, IL) reinterpret_cast<const void *>(k_mfma<kSplitNQ, kSplitNV, kSplitMaxS, 2, true, PK, IL, true>)
+static const void *const kSplitKernels[kKinds] = {nullptr,           PB_SPLIT(1, false), PB_SPLIT(2, false), PB_SPLIT(4, false),
+                                                  PB_SPLIT(1, true), PB_SPLIT(2, true),  PB_SPLIT(4, true)};
+
 // Overrides of the launcher's choices (chunks and vectors per wave, ring depth, workgroups, pairs), for sweeps over
 // the variants: compiled in only with -DPB_TUNING (a tuning build reads them from the environment once); the
 // product build has none and its behaviour does not depend on the environment.  0 / -1 = not set.
 struct Tuning {
-    int nq = 0, nv = 0, ru = 0, wgs = 0, pair = -1;
+    int nq = 0, nv = 0, ru = 0, wgs = 0, pair = -1, split = -1;
 #ifdef PB_TUNING
     Tuning()
     {
         auto get = [](const char *name, int unset) { const char *e = getenv(name); return e ? atoi(e) : unset; };
         nq = get("PB_TUNE_NQ", 0); nv = get("PB_TUNE_NV", 0); ru = get("PB_TUNE_RU", 0);
-        wgs = get("PB_TUNE_WGS", 0); pair = get("PB_TUNE_PAIR", -1);
+        wgs = get("PB_TUNE_WGS", 0); pair = get("PB_TUNE_PAIR", -1); split = get("PB_TUNE_SPLIT", -1);
         if (nq < 0) nq = 0;
         if (nv < 0) nv = 0;
         if (ru < 0) ru = 0;
@@ -1036,6 +1093,26 @@ static int resident_workgroups(int variant, int S, int kind)
     return v;
 }
 
+// The same for the kernels that split the columns (S waves).
+static int resident_split_workgroups(int S, int kind)
+{
+    static int cache[kKinds][kSplitMaxS + 1];
+    int *slot = &cache[kind][S];
+    int v = __atomic_load_n(slot, __ATOMIC_RELAXED);
+    if (v > 0) return v;
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipFuncSetAttribute(kSplitKernels[kind], hipFuncAttributeMaxDynamicSharedMemorySize, (int)stage_bytes(S)) !=
+        hipSuccess)
+        return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kSplitKernels[kind], S * 64, stage_bytes(S)) != hipSuccess)
+        return 0;
+    v = cus * per_cu;
+    if (v > 0) __atomic_store_n(slot, v, __ATOMIC_RELAXED);
+    return v;
+}
+
 int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, int bits_used, int frac_bits,
                 int act_bits, const float *X0, int cols0, const float *X1, int cols1, const uint32_t *planes,
                 int batch, float *Y, long long *A, bool pairs_out, const Epilogue &ep, hipStream_t st)
@@ -1075,6 +1152,32 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     if (L.cols > kMaxColsPairs) return (int)hipErrorInvalidValue;   // (cannot happen: pairs cover every width)
     const int kind = !pair ? kSingle
                            : (pk == 1 ? kPairs : (pk == 2 ? kPairs2 : kPairs4)) + (is_pairs(L.layout) ? kDigits : 0);
+    void *args[] = {&h.packed, &h.X0, &h.packed_bytes, &h.flags, &h.cols0, &h.batch, &h.layer_step, &h.round_step,
+                    &h.rounds_per_wg, &h.rt_count, &h.cq, &h.m, &a};
+    // Rows of more than 8192 columns leave a wave registers for the digit rows of two operands (one beyond 16384
+    // columns): with enough operands to fill, the columns are covered in several passes of four operands.
+    // (Measured, bits_used 8, plain / in passes: 12288 columns: batch 4 45 / 46 us, batch 16 151 / 119 us, batch 64
+    // 561 / 424 us; 16384: batch 4 63 / 61 us, batch 8 113 / 98 us, batch 64 807 / 645 us; 32768: batch 4 594 / 223 us,
+    // batch 64 7.4 / 2.4 ms.)
+    bool split = kSplitKernels[kind] && ((L.cq > 2 * kSplitNQ * kSplitMaxS && slots >= 3) ||
+                                         (L.cq > kSplitNQ * kSplitMaxS && slots >= 5));
+    if (tuning().split >= 0) split = split && tuning().split != 0;
+    if (split) {
+        const int parts = (L.cq + kSplitNQ * kSplitMaxS - 1) / (kSplitNQ * kSplitMaxS);
+        const int S = ((L.cq + parts - 1) / parts + kSplitNQ - 1) / kSplitNQ;
+        const int groups = (slots + kSplitNV - 1) / kSplitNV;
+        int capacity = resident_split_workgroups(S, kind);
+        if (capacity < 1) return (int)hipErrorInvalidValue;
+        if (tuning().wgs > 0) capacity = tuning().wgs;
+        int wgs = capacity / groups;
+        if (wgs < 1) wgs = 1;
+        if (wgs > L.rt_count) wgs = L.rt_count;
+        h.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
+        wgs = (L.rt_count + h.rounds_per_wg - 1) / h.rounds_per_wg;
+        const hipError_t e = hipLaunchKernel(kSplitKernels[kind], dim3((unsigned)wgs, (unsigned)groups),
+                                             dim3((unsigned)S * 64), args, planes ? 0 : stage_bytes(S), st);
+        return (int)(e != hipSuccess ? e : hipGetLastError());
+    }
     int vi = pick_variant(L, slots, kind);
     if (vi < 0) return (int)hipErrorInvalidValue;
     const Variant &var = kVariants[vi];   // (the ring depth does not change a variant's occupancy: same registers +- a few)
@@ -1090,8 +1193,6 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     if (wgs > L.rt_count) wgs = L.rt_count;
     h.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
     wgs = (L.rt_count + h.rounds_per_wg - 1) / h.rounds_per_wg;
-    void *args[] = {&h.packed, &h.X0, &h.packed_bytes, &h.flags, &h.cols0, &h.batch, &h.layer_step, &h.round_step,
-                    &h.rounds_per_wg, &h.rt_count, &h.cq, &h.m, &a};
     const Variant &run = kVariants[pick_ring(vi, h.rounds_per_wg * (pair ? (bits_used + 1) / 2 : bits_used), kind)];
     const hipError_t e = hipLaunchKernel(run.fn[kind], dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64),
                                          args, planes ? 0 : stage_bytes(S), st);

@@ -513,6 +513,64 @@ def test_extra_16384(pb, layout):
         assert_y_close(Y_gpu[:, r], y, sub[:, 0, :], prep["scales"])
 
 
+@pytest.mark.parametrize("lay", TILED)
+def test_wide_rows_in_several_passes(pb, lay):
+    """Rows of more than 8192 columns with three and more operands: the kernel covers the columns in several passes
+    over the same row tiles (here three: 16500 columns), whose sums wait in LDS for the last pass, as many row tiles
+    at a time as have room: 207 row tiles on four or eight workgroups per vector group make every workgroup go
+    through several such rounds, with every kind of sums (groups of pairs, pair by pair, bitlayer by bitlayer with
+    scales that do not halve) and one, two and four vectors per operand.  The oracle computes sampled rows."""
+    R, C, N, bits = 3300, 16500, 256, 8
+    W, X = synth.ragged(R, C, batch=N, case=91, xdist="normal")
+    rng = np.random.default_rng(91)
+    rows = sorted(set(rng.choice(R, size=12, replace=False).tolist() + [0, 15, 16, R - 1]))
+    prep = po.prepare(W, bits)
+    Xd = dev(X)
+    for (act_bits, frac_bits, m) in ((32, 16, 8), (32, 16, 5), (16, 10, 7), (8, 4, 8)):
+        print("wide rows", lay, act_bits, m, flush=True)
+        lin = pb.PackedLinear(dev(W), bits, max_batch=N, frac_bits=frac_bits, act_bits=act_bits, layout=LAYOUTS[lay])
+        Y_gpu = lin(Xd, m).cpu().numpy()
+        P_gpu = lin.acc_pairs(Xd, m).cpu().numpy()
+        sc = prep["scales"].copy()
+        sc[1] = np.nextafter(sc[1], np.float32(1.0))       # one ulp: no pair is merged
+        lin.scales[:bits] = dev(sc)
+        Y2_gpu = lin(Xd, m).cpu().numpy()
+        xq = po.fixed_point(X, frac_bits=frac_bits, act_bits=act_bits)
+        for r in rows:
+            sub = po.layer_products_direct(prep["layers"][:, r:r + 1, :], m, xq)[:, :, 0]      # [m, N]
+            assert (P_gpu[:, :, r] == pair_sums(sub[:, :, None], m)[:, :, 0]).all(), (r, "pair sums")
+            y = po.dequant(sub, prep["scales"], m, frac_bits=frac_bits)
+            assert_y_close(Y_gpu[:, r], y, sub, prep["scales"], frac_bits=frac_bits)
+            y2 = np.zeros(N)
+            for i in range(m):
+                y2 += float(sc[i]) * sub[i].astype(np.float64)
+            assert_y_close(Y2_gpu[:, r], (y2 * 2.0 ** -frac_bits).astype(np.float32), sub, sc, frac_bits=frac_bits)
+
+
+def test_wide_rows_lstm_cell_with_batch(pb):
+    """The fused cell update at the end of the last of two passes over the columns (8440 columns, batch 5)."""
+    H, I, bits, N = 40, 8400, 4, 5
+    g = np.random.default_rng(200300822 + 53)
+    W = g.uniform(-0.01, 0.01, size=(4 * H, I + H)).astype(np.float32)
+    x = g.normal(size=(N, I)).astype(np.float32)
+    h = g.uniform(-1, 1, size=(N, H)).astype(np.float32)
+    c = g.uniform(-1, 1, size=(N, H)).astype(np.float32)
+    bias = g.normal(0, 0.1, size=4 * H).astype(np.float32)
+    prep = po.prepare(W, bits)
+    lw = po.pack_words(prep["layers"])
+    xh = np.concatenate([x, h], axis=1)
+    _, Y = po.matmul_words(lw, prep["scales"], bits, I + H, xh)
+    h_ref, c_ref = po.lstm_pointwise(Y, bias, c)
+    for lay in (GATES, LAYOUTS["mfma"]):
+        lin = pb.PackedLinear(dev(W), bits, max_batch=N, layout=lay)
+        h_out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        c_out = torch.empty((N, H), dtype=torch.float32, device="cuda")
+        pb.pb_lstm_cell(lin.packed, lin.scales, lin.desc, bits, dev(x), I, dev(h), dev(c), dev(bias), h_out, c_out, N,
+                        lin.workspace)
+        assert np.abs(h_out.cpu().numpy() - h_ref).max() <= 2e-6
+        assert np.abs(c_out.cpu().numpy() - c_ref).max() <= 2e-6
+
+
 GATES = 0x50420003
 
 
