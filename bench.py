@@ -621,8 +621,31 @@ def batch_sweep(torch, pb, synth, dev):
                              "us_per_vector": round(t * 1e6 / N, 2),
                              "Tbitmac_per_s": round(float(n) * n * m * k * N / t / 1e12, 1)})
             del lin
+    # rows of 16384 columns: the kernels that take the columns in several passes (batch 16 and 64)
+    del Wd, X, Y
+    nw = 16384
+    W, _ = synth.fc_square(nw, 0.01, batch=1, cfg=6)
+    Wd = torch.from_numpy(W).to(dev)
+    del W
+    X = torch.randn((64, nw), device=dev, generator=gen)
+    Y = torch.empty((64, nw), dtype=torch.float32, device=dev)
+    wide = []
+    for name, lay in (("mfma", pb.PB_LAYOUT_TILE16_V1), ("mfma, pairs layout", pb.PB_LAYOUT_TILE16_PAIRS_V1)):
+        lin = pb.PackedLinear(Wd, B, max_batch=64, layout=lay)
+        for N in (16, 64):
+            def f():
+                pb.pb_matmul(lin.packed, lin.scales, lin.desc, m, X[:N], N, Y[:N], lin.workspace)
+            t = time_calls(f, N)
+            issued = 2.0 * 16 * nw * nw * ((m + 1) // 2) * N / t / 1e12
+            wide.append({"kernel": name, "batch": N, "act_bits": 32, "us_per_call": round(t * 1e6, 1),
+                         "us_per_vector": round(t * 1e6 / N, 2),
+                         "Tbitmac_per_s": round(float(nw) * nw * m * 32 * N / t / 1e12, 1),
+                         "mfma_issued_TFLOPs": round(issued, 1), "mfma_frac": round(issued / FP4_PEAK_TFLOPS, 4)})
+        del lin
     return {"workload": "FC 8192x8192, B=8, bits_used=8, x~N(0,1), batch 1..1024, weights warm",
-            "alu_peak_Gops": round(ALU_PEAK_GOPS, 1), "fp4_peak_TFLOPs": FP4_PEAK_TFLOPS, "rows": rows}
+            "alu_peak_Gops": round(ALU_PEAK_GOPS, 1), "fp4_peak_TFLOPs": FP4_PEAK_TFLOPS, "rows": rows,
+            "wide_rows": {"workload": "FC 16384x16384, B=8, bits_used=8, x~N(0,1), batch 16 and 64, weights warm",
+                          "rows": wide}}
 
 
 def batch_point(torch, pb, synth, dev, n, B, N, steps, layout):
