@@ -302,10 +302,12 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     __shared__ __align__(16) int abuf[SPLIT ? 1 : 2][SPLIT ? 1 : NV][SPLIT ? 1 : PB_MAX_BITS][kTileRows][QN];
     __shared__ __align__(16) int sbuf[SPLIT ? kSplitInts : 4];
     __shared__ float s_scales[PB_MAX_BITS];
+    // merged pairs: what the sign pair's digits count too much, per operand and kind of sum (see below)
+    __shared__ __align__(16) int s_sx[NV][8];
     // staging area of the activation transpose, kStageRows rows of 8 bytes per wave (none when the planes are given)
     extern __shared__ __align__(16) unsigned char stage_lds[];
 
-    const int lane = threadIdx.x & 63;
+    const int lane_id = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // SPLIT: `parts` passes over the columns, each of cq_part chunks (every wave has the same slice in every pass,
     // a wave of the last pass maybe none); the loop below runs pass after pass, round after round.
@@ -320,6 +322,10 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const int mp = PAIR ? (m + 1) / 2 : m;
     int turn = 0;         // (row tiles finished * RW) % nwaves, kept up by additions: the wave whose turn it is to finish a row tile
   for (int rt_base = 0, part = 0;;) {
+    // (SPLIT: the lane number is taken anew in every pass, so that what a pass derives from it is worked out again
+    // instead of occupying registers through the products of the pass before)
+    int lane = lane_id;
+    if constexpr (SPLIT) asm volatile("" : "+v"(lane));
     const int q0 = (part * nwaves + wave) * NQ;                 // first chunk of this wave's column slice
     const int nq = min(NQ, h.cq - q0);                          // chunks it really has (>= 1 by construction; SPLIT: maybe none)
     const int rt0 = rt_first + rt_base;
@@ -390,11 +396,14 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     auto zero_sums_and_meet = [&]() {
         if constexpr (SPLIT) {
             // (later passes find the sums of the passes before them, or the zeros that the final sums left)
-            if (rt_base == 0 && part == 0)
+            if (rt_base == 0 && part == 0) {
                 for (int i = threadIdx.x; i < kSplitInts; i += nwaves * 64) sbuf[i] = 0;
+                if (threadIdx.x < NV * 8) (&s_sx[0][0])[threadIdx.x] = 0;
+            }
         } else {
             for (int i = threadIdx.x; i < 2 * NV * PB_MAX_BITS * QN * kTileRows; i += nwaves * 64)
                 (&abuf[0][0][0][0][0])[i] = 0;
+            if (threadIdx.x < NV * 8) (&s_sx[0][0])[threadIdx.x] = 0;
         }
         __builtin_amdgcn_sched_barrier(0);
         __syncthreads();
@@ -639,13 +648,11 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     auto layer_scale = [&](int layer) {
         return layer < m ? s_scales[layer] : (m == 1 ? -0.5f : 0.5f) * s_scales[m - 1];
     };
-    // sum_c x_q[c] over the slice, as this lane's share of it in the form of the group sums: the product with an
-    // operand of digits 1, doubled (the digits of the sign pair stand 2 too high in every column) and with the
-    // factor of pair 0 in its group
-    int sxc[NV][2];
-#pragma unroll
-    for (int v = 0; v < NV; ++v) sxc[v][0] = sxc[v][1] = 0;
-    if (PAIR && merged && (IL || m >= 2)) {
+    // sum_c x_q[c] over the slice, in the form of the group sums: the product with an operand of digits 1, doubled
+    // (the digits of the sign pair stand 2 too high in every column) and with the factor of pair 0 in its group.
+    // It is the same for every row: the slices add theirs up in LDS once per call (SPLIT: every pass of the first
+    // round its columns') and the final sum takes it off the first group of every row.
+    if (PAIR && merged && (IL || m >= 2) && (!SPLIT || rt_base == 0)) {
         const v8i ones = {0x11111111, 0x11111111, 0x11111111, 0x11111111, 0, 0, 0, 0};
         const int e0 = low_layer(min(gsize, mp) - 1) - 1 + 1;   // (+ 1: doubled)
 #pragma unroll
@@ -655,23 +662,25 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
             for (int q = 0; q < NQ; ++q)
 #pragma unroll
                 for (int t = 0; t < 4; ++t) acc = mfma_fp4(as_operand(pa[v][q][t]), ones, acc, 128, 128);
-            sxc[v][0] = ((int)acc[0] + ((int)acc[1] << 4)) << e0;
-            sxc[v][1] = ((int)acc[2] + ((int)acc[3] << 4)) << e0;
+            int s0 = ((int)acc[0] + ((int)acc[1] << 4)) << e0, s1 = ((int)acc[2] + ((int)acc[3] << 4)) << e0;
+            // (the matrix instructions need every lane: the sums are pinned here so that the compiler does not move
+            // their computation into the branch of the lanes that add them up, as it did)
+            asm volatile("" : "+v"(s0), "+v"(s1));
+            if (j == 0) {
+                atomicAdd(&s_sx[v][2 * kb], s0);
+                atomicAdd(&s_sx[v][2 * kb + 1], s1);
+            }
         }
     }
     v4f accg[NV];         // the sums of the group being multiplied
     int gfirst = 0, gset = 0;   // its first pair, its index in the row tile
     // the end of a group: its sums go to LDS, eight integers per (operand, group, row): word 2 kb + e is the half e
     // of the lanes of kind kb
-    auto finish_group = [&](bool sign_group) {
+    auto finish_group = [&]() {
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            int i0 = (int)accg[v][0] + ((int)accg[v][1] << 4);
-            int i1 = (int)accg[v][2] + ((int)accg[v][3] << 4);
-            if (sign_group) {
-                i0 -= sxc[v][0];
-                i1 -= sxc[v][1];
-            }
+            const int i0 = (int)accg[v][0] + ((int)accg[v][1] << 4);
+            const int i1 = (int)accg[v][2] + ((int)accg[v][3] << 4);
             int *dst = sums_of(v) + gset * (kTileRows * 8) + j * 8 + 2 * kb;
             atomicAdd(dst, i0);
             atomicAdd(dst + 1, i1);
@@ -715,7 +724,7 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                         }
                     }
                     if (pp == glast) {
-                        finish_group(gfirst == 0 && (IL || m >= 2));
+                        finish_group();
                         gfirst += gsize;
                         ++gset;
                     }
@@ -799,7 +808,13 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
                                 int4 *g4 = reinterpret_cast<int4 *>(grp + g * (kTileRows * 8));
                                 const int4 t0 = g4[0], t1 = g4[1];
                                 g4[0] = g4[1] = make_int4(0, 0, 0, 0);
-                                const int w[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+                                int w[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
+                                if (g == 0) {   // the sign pair's group (zeros if there is nothing to take off)
+                                    const int4 *sx4 = reinterpret_cast<const int4 *>(&s_sx[v < NV ? v : 0][0]);
+                                    const int4 x0 = sx4[0], x1 = sx4[1];
+                                    w[0] -= x0.x; w[1] -= x0.y; w[2] -= x0.z; w[3] -= x0.w;
+                                    w[4] -= x1.x; w[5] -= x1.y; w[6] -= x1.z; w[7] -= x1.w;
+                                }
                                 // the group carries the scale of the low bitlayer of its last pair
                                 const int si = low_layer(min((g + 1) * gsize, mp) - 1);
                                 // (IL, sums of the pairs asked for) a single bitlayer came as twice itself, the sign
@@ -1161,7 +1176,7 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     // batch 64 7.4 / 2.4 ms.)
     bool split = kSplitKernels[kind] && ((L.cq > 2 * kSplitNQ * kSplitMaxS && slots >= 3) ||
                                          (L.cq > kSplitNQ * kSplitMaxS && slots >= 5));
-    if (tuning().split >= 0) split = split && tuning().split != 0;
+    if (tuning().split >= 0) split = kSplitKernels[kind] && slots >= 3 && tuning().split != 0;
     if (split) {
         const int parts = (L.cq + kSplitNQ * kSplitMaxS - 1) / (kSplitNQ * kSplitMaxS);
         const int S = ((L.cq + parts - 1) / parts + kSplitNQ - 1) / kSplitNQ;
