@@ -61,7 +61,9 @@ def test_partial_sums_fit_at_the_widest_matrix(limits, pairs):
     slice_cols = limits["cols"] // limits["slices"]        # columns of one wave's slice at the widest matrix
     assert slice_cols == 2048
     # weight digit of every column: 0/1 for a single bitlayer; 2 w_hi + w_lo = 0..3 for a pair; the sign pair enters
-    # as 2 (1 - w_0) + w_1 = 0..3 and the kernel subtracts 2 * sum_c x_q[c] afterwards
+    # as 2 (1 - w_0) + w_1 = 0..3 and 2 * sum_c x_q[c] is taken off afterwards.  (The kernel keeps the sums of merged
+    # pairs as the two halves of the next test; the single word per lane checked here is the tighter form, which a
+    # pair by itself would still fit.)
     wdigits = [1] if not pairs else [1, 2, 3]
     for xq, wd, sign_pair in itertools.product(SATURATED, wdigits, [False, True] if pairs else [False]):
         d = digits_of(xq)
@@ -113,14 +115,19 @@ def test_group_sums_fit_at_the_widest_matrix(limits, last_is_single):
             assert all(fits_fp32_exactly(a) for a in acc), (hex(xq & 0xFFFFFFFF), acc)
             i0, i1 = acc[0] + 16 * acc[1], acc[2] + 16 * acc[3]       # converted register by register, as integers
             assert fits_int32(i0) and fits_int32(i1)
-            if with_sign_pair:      # pair 0 of the group is the sign pair: minus 2 * sum_c x_q[c], times its factor
-                ones = [d[b + 2 * c] * slice_cols for c in range(4)]
-                s0, s1 = (ones[0] + 16 * ones[1]) * 2 * factors[0], (ones[2] + 16 * ones[3]) * 2 * factors[0]
-                assert fits_int32(s0) and fits_int32(s1)
-                i0, i1 = i0 - s0, i1 - s1
-                assert fits_int32(i0) and fits_int32(i1)
             w0, w1 = i0 * cols // slice_cols, i1 * cols // slice_cols      # the LDS words: all slices of a row
             assert fits_int32(w0) and fits_int32(w1), (hex(xq & 0xFFFFFFFF), b, w0, w1)
+            if with_sign_pair:
+                # pair 0 of the group is the sign pair: 2 * sum_c x_q[c] times its factor is what its digits count too
+                # much; the slices add their shares up in LDS words of the same form, once per call, and the final sum
+                # takes them off the row's words
+                ones = [d[b + 2 * c] * slice_cols for c in range(4)]
+                s0, s1 = (ones[0] + 16 * ones[1]) * 2 * factors[0], (ones[2] + 16 * ones[3]) * 2 * factors[0]
+                assert fits_int32(s0) and fits_int32(s1)                       # a slice's share
+                s0, s1 = s0 * cols // slice_cols, s1 * cols // slice_cols
+                assert fits_int32(s0) and fits_int32(s1), (hex(xq & 0xFFFFFFFF), b, s0, s1)
+                w0, w1 = w0 - s0, w1 - s1
+                assert fits_int32(w0) and fits_int32(w1)
             halves.append(w0 + 256 * w1)
         total = halves[0] + 4 * halves[2] + ((halves[1] + 4 * halves[3]) << 16)
         signed = xq if xq < 2 ** 31 else xq - 2 ** 32
