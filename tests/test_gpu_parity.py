@@ -786,3 +786,40 @@ def test_graph_replay_matches_eager(pb):
         assert torch.isfinite(junk)
         for a_, b_ in zip(got, (y2, h_out, c_out)):
             assert torch.equal(a_, b_), "replay %d differs from the eager run" % it
+
+
+def test_graph_replay_of_wide_rows(pb):
+    """The kernels that take wide rows in several passes keep sums in LDS from pass to pass: a captured call (9000
+    columns, batch 6, 70 row tiles) replayed with new inputs, eager calls of other shapes in between, gives the eager
+    result bit for bit."""
+    rng = np.random.default_rng(78)
+    W, X = synth.ragged(1100, 9000, batch=6, case=54, xdist="normal")
+    lin = pb.PackedLinear(dev(W), 6, max_batch=6, layout=LAYOUTS["pair"])
+    Ws, Xs = synth.ragged(40, 700, batch=2, case=55)
+    small = pb.PackedLinear(dev(Ws), 4, max_batch=2)
+    x = dev(X)
+    xs = dev(Xs)
+    y = torch.empty((6, 1100), device="cuda")
+    bias = dev(rng.normal(size=1100).astype(np.float32))
+
+    def call():
+        pb.pb_matmul_bias_act(lin.packed, lin.scales, lin.desc, 5, x, 6, bias, pb.PB_ACT_RELU, y, lin.workspace)
+
+    call()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        call()
+    for it in range(4):
+        x.copy_(dev(rng.normal(size=X.shape).astype(np.float32)))
+        g.replay()
+        torch.cuda.synchronize()
+        got = y.clone()
+        small(xs, 3)                                        # other work between the replays
+        call()
+        torch.cuda.synchronize()
+        assert torch.equal(got, y), "replay %d differs from the eager run" % it
+    ref = oracle_reference(W, 6, x.cpu().numpy(), 5)
+    want = np.maximum(ref["Y"] + bias.cpu().numpy()[None, :], 0)
+    assert np.abs(y.cpu().numpy() - want).max() <= 1e-5 * np.abs(want).max()
+

@@ -41,8 +41,9 @@ def test_static_scratch_matches_pb_matmul_twice(pb, layout_name):
     layout = {"popc": pb.PB_LAYOUT_ROWMAJOR_V1, "mfma": pb.PB_LAYOUT_TILE16_V1,
               "pair": pb.PB_LAYOUT_TILE16_PAIRS_V1}[layout_name]
     bits = 6
-    # first call: 300 x 2100, batch 5; second call: a smaller matrix and batch (the scratch keeps the first call's planes)
-    for (R, C, N, m, case) in ((300, 2100, 5, 6, 61), (70, 500, 2, 3, 62)):
+    # first call: 300 x 2100, batch 5; then rows wide enough for the kernels that take the columns in two passes;
+    # last a smaller matrix and batch (the scratch keeps the earlier calls' planes)
+    for (R, C, N, m, case) in ((300, 2100, 5, 6, 61), (90, 9000, 6, 5, 63), (70, 500, 2, 3, 62)):
         print("static scratch", layout_name, R, C, N, flush=True)
         W, X = synth.ragged(R, C, batch=N, case=case, xdist="wide")
         lin = pb.PackedLinear(dev(W), bits, max_batch=N, layout=layout)
