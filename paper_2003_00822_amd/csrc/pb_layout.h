@@ -54,6 +54,18 @@ constexpr int kMaxColsPairs = 32768;
 // 17 * 9 * 32768 * 341 < 2^31.
 constexpr int kPairGroup = 5;
 
+// Rows wider than the digit rows a workgroup of the matrix-core kernel can hold for four operands are covered in
+// several passes over the columns (batches only): at most kSplitChunks chunks of 512 columns per pass (eight waves
+// with two chunks each), the chunks shared out evenly.  The launcher sizes the workgroup with these and the kernel
+// finds its slice with them.
+constexpr int kSplitChunks = 16;
+__host__ __device__ inline int split_parts(int cq) { return (cq + kSplitChunks - 1) / kSplitChunks; }
+__host__ __device__ inline int split_chunks_per_part(int cq)
+{
+    const int parts = split_parts(cq);
+    return (cq + parts - 1) / parts;
+}
+
 struct Layout {
     uint32_t layout;
     int rows, cols, bits;

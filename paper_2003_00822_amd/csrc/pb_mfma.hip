@@ -311,8 +311,9 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // SPLIT: `parts` passes over the columns, each of cq_part chunks (every wave has the same slice in every pass,
     // a wave of the last pass maybe none); the loop below runs pass after pass, round after round.
-    const int parts = SPLIT ? (h.cq + MAXS * NQ - 1) / (MAXS * NQ) : 1;
-    const int cq_part = SPLIT ? (h.cq + parts - 1) / parts : h.cq;   // chunks per pass
+    static_assert(!SPLIT || MAXS * NQ == kSplitChunks, "a pass covers kSplitChunks chunks at most");
+    const int parts = SPLIT ? split_parts(h.cq) : 1;
+    const int cq_part = SPLIT ? split_chunks_per_part(h.cq) : h.cq;   // chunks per pass
     const int nwaves = (cq_part + NQ - 1) / NQ;                 // = blockDim.x / 64 (the launcher's S), from a preloaded argument
     const int n0 = blockIdx.y * NV * PK;                        // first activation vector of this workgroup
     const int m = h.m;
@@ -1006,6 +1007,7 @@ constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 // The kernels that cover rows of more than 8192 columns in several passes (two chunks and four operands per wave,
 // eight waves, two units in flight), by kind: pair kernels only.
 constexpr int kSplitNQ = 2, kSplitNV = 4, kSplitMaxS = 8;
+static_assert(kSplitNQ * kSplitMaxS == kSplitChunks, "the chunks of a pass are those of eight waves");
 #define PB_SPLIT(PK, IL) reinterpret_cast<const void *>(k_mfma<kSplitNQ, kSplitNV, kSplitMaxS, 2, true, PK, IL, true>)
 static const void *const kSplitKernels[kKinds] = {nullptr,           PB_SPLIT(1, false), PB_SPLIT(2, false), PB_SPLIT(4, false),
                                                   PB_SPLIT(1, true), PB_SPLIT(2, true),  PB_SPLIT(4, true)};
@@ -1174,12 +1176,10 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     // (Measured, bits_used 8, plain / in passes: 12288 columns: batch 4 45 / 46 us, batch 16 151 / 119 us, batch 64
     // 561 / 424 us; 16384: batch 4 63 / 61 us, batch 8 113 / 98 us, batch 64 807 / 645 us; 32768: batch 4 594 / 223 us,
     // batch 64 7.4 / 2.4 ms.)
-    bool split = kSplitKernels[kind] && ((L.cq > 2 * kSplitNQ * kSplitMaxS && slots >= 3) ||
-                                         (L.cq > kSplitNQ * kSplitMaxS && slots >= 5));
+    bool split = kSplitKernels[kind] && ((L.cq > 2 * kSplitChunks && slots >= 3) || (L.cq > kSplitChunks && slots >= 5));
     if (tuning().split >= 0) split = kSplitKernels[kind] && slots >= 3 && tuning().split != 0;
     if (split) {
-        const int parts = (L.cq + kSplitNQ * kSplitMaxS - 1) / (kSplitNQ * kSplitMaxS);
-        const int S = ((L.cq + parts - 1) / parts + kSplitNQ - 1) / kSplitNQ;
+        const int S = (split_chunks_per_part(L.cq) + kSplitNQ - 1) / kSplitNQ;
         const int groups = (slots + kSplitNV - 1) / kSplitNV;
         int capacity = resident_split_workgroups(S, kind);
         if (capacity < 1) return (int)hipErrorInvalidValue;

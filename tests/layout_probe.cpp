@@ -53,4 +53,12 @@ void probe_pair_digits(unsigned upper, unsigned lower, unsigned *out)
     pb::pair_of_digits(out[0], out[1], &out[2], &out[3]);
 }
 
+// wide rows in several passes: out = {most chunks per pass, passes, chunks per pass} for a row of cq chunks
+void probe_split(int cq, int *out)
+{
+    out[0] = pb::kSplitChunks;
+    out[1] = pb::split_parts(cq);
+    out[2] = pb::split_chunks_per_part(cq);
+}
+
 }  // extern "C"

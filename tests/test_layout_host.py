@@ -150,3 +150,25 @@ def test_workspace_grows_with_batch(probe):
     a = probe.probe_workspace_bytes(TILE16, 100, 3000, 3, 1)
     b = probe.probe_workspace_bytes(TILE16, 100, 3000, 3, 7)
     assert a > 0 and b > a and a % 256 == 0 and b % 256 == 0
+
+
+
+def test_passes_over_wide_rows(probe):
+    """The geometry that the launcher and the matrix-core kernel share when batches on wide rows take the columns
+    in several passes: every chunk belongs to exactly one pass, a pass never has more chunks than eight waves with
+    two chunks each hold, the passes are as few as that allows and evenly filled, and rows of up to 16 chunks need one."""
+    out = (ctypes.c_int * 3)()
+    widest = layout_of(probe, TILE16, 16, 32768, 8)["cq"]
+    assert widest == 64
+    for cq in range(1, widest + 1):
+        probe.probe_split(cq, out)
+        cap, parts, per = list(out)
+        assert cap == 16
+        assert parts == -(-cq // cap) and 1 <= parts <= 4
+        assert per <= cap and parts * per >= cq > (parts - 1) * per
+        waves = -(-per // 2)
+        assert 1 <= waves <= 8
+        # wave w of pass p owns the chunks 2 (p * waves + w), + 1: all chunks covered once, none beyond the last pass
+        owned = [2 * (p * waves + w) + k for p in range(parts) for w in range(waves) for k in range(2)]
+        assert sorted(set(owned)) == owned and set(range(cq)) <= set(owned)
+
