@@ -54,15 +54,15 @@ constexpr int kMaxColsPairs = 32768;
 // 17 * 9 * 32768 * 341 < 2^31.
 constexpr int kPairGroup = 5;
 
-// Rows wider than the digit rows a workgroup of the matrix-core kernel can hold for four operands are covered in
-// several passes over the columns (batches only): at most kSplitChunks chunks of 512 columns per pass (eight waves
-// with two chunks each), the chunks shared out evenly.  The launcher sizes the workgroup with these and the kernel
-// finds its slice with them.
-constexpr int kSplitChunks = 16;
-__host__ __device__ inline int split_parts(int cq) { return (cq + kSplitChunks - 1) / kSplitChunks; }
-__host__ __device__ inline int split_chunks_per_part(int cq)
+// Batches on rows wider than the digit rows that the waves of a workgroup of the matrix-core kernel hold are
+// covered in several passes over the columns: at most `cap` chunks of 512 columns per pass (what eight waves hold:
+// kSplitChunks4 with four operands per wave, kSplitChunks8 with eight), the chunks shared out evenly.  The launcher
+// sizes the workgroup with these and the kernel finds its slice with them.
+constexpr int kSplitChunks4 = 16, kSplitChunks8 = 8;
+__host__ __device__ inline int split_parts(int cq, int cap) { return (cq + cap - 1) / cap; }
+__host__ __device__ inline int split_chunks_per_part(int cq, int cap)
 {
-    const int parts = split_parts(cq);
+    const int parts = split_parts(cq, cap);
     return (cq + parts - 1) / parts;
 }
 

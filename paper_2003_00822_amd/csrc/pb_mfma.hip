@@ -311,9 +311,8 @@ __global__ __launch_bounds__(MAXS * 64) void k_mfma(const uint32_t *packed, cons
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // SPLIT: `parts` passes over the columns, each of cq_part chunks (every wave has the same slice in every pass,
     // a wave of the last pass maybe none); the loop below runs pass after pass, round after round.
-    static_assert(!SPLIT || MAXS * NQ == kSplitChunks, "a pass covers kSplitChunks chunks at most");
-    const int parts = SPLIT ? split_parts(h.cq) : 1;
-    const int cq_part = SPLIT ? split_chunks_per_part(h.cq) : h.cq;   // chunks per pass
+    const int parts = SPLIT ? split_parts(h.cq, MAXS * NQ) : 1;
+    const int cq_part = SPLIT ? split_chunks_per_part(h.cq, MAXS * NQ) : h.cq;   // chunks per pass
     const int nwaves = (cq_part + NQ - 1) / NQ;                 // = blockDim.x / 64 (the launcher's S), from a preloaded argument
     const int n0 = blockIdx.y * NV * PK;                        // first activation vector of this workgroup
     const int m = h.m;
@@ -1004,13 +1003,23 @@ static const Variant kVariants[] = {
 };
 constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
 
-// The kernels that cover rows of more than 8192 columns in several passes (two chunks and four operands per wave,
-// eight waves, two units in flight), by kind: pair kernels only.
-constexpr int kSplitNQ = 2, kSplitNV = 4, kSplitMaxS = 8;
-static_assert(kSplitNQ * kSplitMaxS == kSplitChunks, "the chunks of a pass are those of eight waves");
-#define PB_SPLIT(PK, IL) reinterpret_cast<const void *>(k_mfma<kSplitNQ, kSplitNV, kSplitMaxS, 2, true, PK, IL, true>)
-static const void *const kSplitKernels[kKinds] = {nullptr,           PB_SPLIT(1, false), PB_SPLIT(2, false), PB_SPLIT(4, false),
-                                                  PB_SPLIT(1, true), PB_SPLIT(2, true),  PB_SPLIT(4, true)};
+// The kernels that cover wide rows in several passes, by kind (pair kernels only), in two shapes: two chunks and
+// four operands per wave (passes of 8192 columns), one chunk and eight operands per wave (passes of 4096 columns);
+// eight waves, two units in flight.  (With eight operands there is no kind with four vectors per operand: its sums
+// would leave the LDS room for a single row tile per round.)
+struct SplitShape {
+    int nq, nv, chunks;
+    const void *fn[kKinds];
+};
+constexpr int kSplitMaxS = 8;
+#define PB_SPLIT(NQ, NV, PK, IL) reinterpret_cast<const void *>(k_mfma<NQ, NV, kSplitMaxS, 2, true, PK, IL, true>)
+static const SplitShape kSplitShapes[2] = {
+    {2, 4, kSplitChunks4, {nullptr, PB_SPLIT(2, 4, 1, false), PB_SPLIT(2, 4, 2, false), PB_SPLIT(2, 4, 4, false),
+                           PB_SPLIT(2, 4, 1, true), PB_SPLIT(2, 4, 2, true), PB_SPLIT(2, 4, 4, true)}},
+    {1, 8, kSplitChunks8, {nullptr, PB_SPLIT(1, 8, 1, false), PB_SPLIT(1, 8, 2, false), nullptr,
+                           PB_SPLIT(1, 8, 1, true), PB_SPLIT(1, 8, 2, true), nullptr}},
+};
+static_assert(2 * kSplitMaxS == kSplitChunks4 && 1 * kSplitMaxS == kSplitChunks8, "the chunks of a pass are those of eight waves");
 
 // Overrides of the launcher's choices (chunks and vectors per wave, ring depth, workgroups, pairs), for sweeps over
 // the variants: compiled in only with -DPB_TUNING (a tuning build reads them from the environment once); the
@@ -1111,20 +1120,18 @@ static int resident_workgroups(int variant, int S, int kind)
 }
 
 // The same for the kernels that split the columns (S waves).
-static int resident_split_workgroups(int S, int kind)
+static int resident_split_workgroups(int shape, int S, int kind)
 {
-    static int cache[kKinds][kSplitMaxS + 1];
-    int *slot = &cache[kind][S];
+    static int cache[2][kKinds][kSplitMaxS + 1];
+    int *slot = &cache[shape][kind][S];
+    const void *fn = kSplitShapes[shape].fn[kind];
     int v = __atomic_load_n(slot, __ATOMIC_RELAXED);
     if (v > 0) return v;
     int dev = 0, cus = 0, per_cu = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
-    if (hipFuncSetAttribute(kSplitKernels[kind], hipFuncAttributeMaxDynamicSharedMemorySize, (int)stage_bytes(S)) !=
-        hipSuccess)
-        return 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kSplitKernels[kind], S * 64, stage_bytes(S)) != hipSuccess)
-        return 0;
+    if (hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)stage_bytes(S)) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, fn, S * 64, stage_bytes(S)) != hipSuccess) return 0;
     v = cus * per_cu;
     if (v > 0) __atomic_store_n(slot, v, __ATOMIC_RELAXED);
     return v;
@@ -1171,17 +1178,40 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
                            : (pk == 1 ? kPairs : (pk == 2 ? kPairs2 : kPairs4)) + (is_pairs(L.layout) ? kDigits : 0);
     void *args[] = {&h.packed, &h.X0, &h.packed_bytes, &h.flags, &h.cols0, &h.batch, &h.layer_step, &h.round_step,
                     &h.rounds_per_wg, &h.rt_count, &h.cq, &h.m, &a};
-    // Rows of more than 8192 columns leave a wave registers for the digit rows of two operands (one beyond 16384
-    // columns): with enough operands to fill, the columns are covered in several passes of four operands.
-    // (Measured, bits_used 8, plain / in passes: 12288 columns: batch 4 45 / 46 us, batch 16 151 / 119 us, batch 64
-    // 561 / 424 us; 16384: batch 4 63 / 61 us, batch 8 113 / 98 us, batch 64 807 / 645 us; 32768: batch 4 594 / 223 us,
-    // batch 64 7.4 / 2.4 ms.)
-    bool split = kSplitKernels[kind] && ((L.cq > 2 * kSplitChunks && slots >= 3) || (L.cq > kSplitChunks && slots >= 5));
-    if (tuning().split >= 0) split = kSplitKernels[kind] && slots >= 3 && tuning().split != 0;
-    if (split) {
-        const int S = (split_chunks_per_part(L.cq) + kSplitNQ - 1) / kSplitNQ;
-        const int groups = (slots + kSplitNV - 1) / kSplitNV;
-        int capacity = resident_split_workgroups(S, kind);
+    // Batches on wide rows take the columns in several passes (see SplitShape).
+    // Beyond 8192 columns a wave has registers for the digit rows of two operands only (one beyond 16384 columns):
+    // passes of four operands from five operands on (three beyond 16384 columns), of eight operands from seventeen on,
+    // or earlier if that fills the workgroup with more waves (12288 columns: six waves with passes of 8192 columns,
+    // eight with passes of 4096).  Up to 8192 columns the bit layout gains from eight operands per expanded word from
+    // 33 operands on; the digit layout, whose expansion is cheaper, does not.
+    // (Measured, bits_used 8, us per call.  Plain / passes of four: 16384 columns: batch 4 63 / 61, batch 8 113 / 98,
+    // batch 64 807 / 645; 32768: batch 4 594 / 223, batch 64 7400 / 2400.  Passes of four / of eight, bit layout |
+    // digit layout: 16384: batch 12 137 / 145 | 125 / 135, batch 24 270 / 225 | 240 / 209, batch 64 586 / 504 |
+    // 502 / 475; 12288: batch 8 66 / 57 | 58 / 54, batch 64 398 / 289 | 342 / 263.  Plain / passes of eight at 8192:
+    // batch 24 65 / 68, batch 32 79 / 77, batch 48 123 / 113, batch 64 156 / 136, batch 1024 2104 / 1873 | digit
+    // layout: batch 32 68 / 72, batch 64 130 / 128, batch 1024 1778 / 1749.)
+    int shape = -1;
+    {
+        const bool has4 = kSplitShapes[0].fn[kind] != nullptr, has8 = kSplitShapes[1].fn[kind] != nullptr;
+        if (L.cq > kSplitChunks4) {
+            const int waves4 = (split_chunks_per_part(L.cq, kSplitChunks4) + 1) / 2;
+            const int waves8 = split_chunks_per_part(L.cq, kSplitChunks8);
+            if (has8 && (slots >= 17 || (slots >= 5 && waves8 > waves4))) shape = 1;
+            else if (has4 && (slots >= 5 || (L.cq > 2 * kSplitChunks4 && slots >= 3))) shape = 0;
+        } else if (L.cq > kSplitChunks8 && has8 && !is_pairs(L.layout) && slots >= 33) {
+            shape = 1;
+        }
+    }
+    if (tuning().split >= 0) {
+        shape = -1;
+        if (tuning().split == 4 && kSplitShapes[0].fn[kind] && slots >= 3) shape = 0;
+        if (tuning().split == 8 && kSplitShapes[1].fn[kind] && slots >= 5) shape = 1;
+    }
+    if (shape >= 0) {
+        const SplitShape &sh = kSplitShapes[shape];
+        const int S = (split_chunks_per_part(L.cq, sh.chunks) + sh.nq - 1) / sh.nq;
+        const int groups = (slots + sh.nv - 1) / sh.nv;
+        int capacity = resident_split_workgroups(shape, S, kind);
         if (capacity < 1) return (int)hipErrorInvalidValue;
         if (tuning().wgs > 0) capacity = tuning().wgs;
         int wgs = capacity / groups;
@@ -1189,8 +1219,8 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
         if (wgs > L.rt_count) wgs = L.rt_count;
         h.rounds_per_wg = (L.rt_count + wgs - 1) / wgs;
         wgs = (L.rt_count + h.rounds_per_wg - 1) / h.rounds_per_wg;
-        const hipError_t e = hipLaunchKernel(kSplitKernels[kind], dim3((unsigned)wgs, (unsigned)groups),
-                                             dim3((unsigned)S * 64), args, planes ? 0 : stage_bytes(S), st);
+        const hipError_t e = hipLaunchKernel(sh.fn[kind], dim3((unsigned)wgs, (unsigned)groups), dim3((unsigned)S * 64),
+                                             args, planes ? 0 : stage_bytes(S), st);
         return (int)(e != hipSuccess ? e : hipGetLastError());
     }
     int vi = pick_variant(L, slots, kind);

@@ -53,12 +53,16 @@ void probe_pair_digits(unsigned upper, unsigned lower, unsigned *out)
     pb::pair_of_digits(out[0], out[1], &out[2], &out[3]);
 }
 
-// wide rows in several passes: out = {most chunks per pass, passes, chunks per pass} for a row of cq chunks
-void probe_split(int cq, int *out)
+// wide rows in several passes of at most cap chunks: out = {passes, chunks per pass} for a row of cq chunks
+void probe_split(int cq, int cap, int *out)
 {
-    out[0] = pb::kSplitChunks;
-    out[1] = pb::split_parts(cq);
-    out[2] = pb::split_chunks_per_part(cq);
+    out[0] = pb::split_parts(cq, cap);
+    out[1] = pb::split_chunks_per_part(cq, cap);
+}
+void probe_split_caps(int *out)
+{
+    out[0] = pb::kSplitChunks4;
+    out[1] = pb::kSplitChunks8;
 }
 
 }  // extern "C"

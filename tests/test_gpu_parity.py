@@ -515,11 +515,12 @@ def test_extra_16384(pb, layout):
 
 @pytest.mark.parametrize("lay", TILED)
 def test_wide_rows_in_several_passes(pb, lay):
-    """Rows of more than 8192 columns with three and more operands: the kernel covers the columns in several passes
-    over the same row tiles (here three: 16500 columns), whose sums wait in LDS for the last pass, as many row tiles
-    at a time as have room: 207 row tiles on four or eight workgroups per vector group make every workgroup go
-    through several such rounds, with every kind of sums (groups of pairs, pair by pair, bitlayer by bitlayer with
-    scales that do not halve) and one, two and four vectors per operand.  The oracle computes sampled rows."""
+    """Batches on rows of more than 8192 columns: the kernel covers the columns in several passes over the same row
+    tiles (16500 columns: five passes of eight operands per wave, or three of four operands where four vectors share
+    an operand), whose sums wait in LDS for the last pass, as many row tiles at a time as have room: 207 row tiles
+    on a few workgroups per vector group make every workgroup go through several such rounds, with every kind of
+    sums (groups of pairs, pair by pair, bitlayer by bitlayer with scales that do not halve) and one, two and four
+    vectors per operand.  The oracle computes sampled rows."""
     R, C, N, bits = 3300, 16500, 256, 8
     W, X = synth.ragged(R, C, batch=N, case=91, xdist="normal")
     rng = np.random.default_rng(91)

@@ -155,20 +155,23 @@ def test_workspace_grows_with_batch(probe):
 
 def test_passes_over_wide_rows(probe):
     """The geometry that the launcher and the matrix-core kernel share when batches on wide rows take the columns
-    in several passes: every chunk belongs to exactly one pass, a pass never has more chunks than eight waves with
-    two chunks each hold, the passes are as few as that allows and evenly filled, and rows of up to 16 chunks need one."""
-    out = (ctypes.c_int * 3)()
+    in several passes (of what eight waves hold: 16 chunks with two chunks per wave, 8 with one): every chunk belongs
+    to exactly one pass, a pass never has more chunks than its capacity, the passes are as few as that allows and
+    evenly filled, and a row within the capacity needs one."""
+    caps = (ctypes.c_int * 2)()
+    probe.probe_split_caps(caps)
+    assert list(caps) == [16, 8]
+    out = (ctypes.c_int * 2)()
     widest = layout_of(probe, TILE16, 16, 32768, 8)["cq"]
     assert widest == 64
-    for cq in range(1, widest + 1):
-        probe.probe_split(cq, out)
-        cap, parts, per = list(out)
-        assert cap == 16
-        assert parts == -(-cq // cap) and 1 <= parts <= 4
-        assert per <= cap and parts * per >= cq > (parts - 1) * per
-        waves = -(-per // 2)
-        assert 1 <= waves <= 8
-        # wave w of pass p owns the chunks 2 (p * waves + w), + 1: all chunks covered once, none beyond the last pass
-        owned = [2 * (p * waves + w) + k for p in range(parts) for w in range(waves) for k in range(2)]
-        assert sorted(set(owned)) == owned and set(range(cq)) <= set(owned)
-
+    for cap, per_wave in ((16, 2), (8, 1)):
+        for cq in range(1, widest + 1):
+            probe.probe_split(cq, cap, out)
+            parts, per = list(out)
+            assert parts == -(-cq // cap) and 1 <= parts <= widest // cap
+            assert per <= cap and parts * per >= cq > (parts - 1) * per
+            waves = -(-per // per_wave)
+            assert 1 <= waves <= 8
+            # wave w of pass p owns per_wave chunks from per_wave (p * waves + w): all chunks once, in order
+            owned = [per_wave * (p * waves + w) + k for p in range(parts) for w in range(waves) for k in range(per_wave)]
+            assert sorted(set(owned)) == owned and set(range(cq)) <= set(owned)
