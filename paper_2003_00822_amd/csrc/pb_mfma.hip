@@ -1193,12 +1193,16 @@ int launch_mfma(const uint32_t *packed, const float *scales, const Layout &L, in
     int shape = -1;
     {
         const bool has4 = kSplitShapes[0].fn[kind] != nullptr, has8 = kSplitShapes[1].fn[kind] != nullptr;
+        // (groups of eight must not leave many more operand places empty than groups of four would: 33 operands are
+        // five groups of eight or nine of four, and 16-bit activations at batch 66, 33 operands, took 110 us in
+        // groups of eight against 96 us)
+        const bool fills8 = 8 * ((slots + 7) / 8) * 100 <= 4 * ((slots + 3) / 4) * 108;
         if (L.cq > kSplitChunks4) {
             const int waves4 = (split_chunks_per_part(L.cq, kSplitChunks4) + 1) / 2;
             const int waves8 = split_chunks_per_part(L.cq, kSplitChunks8);
-            if (has8 && (slots >= 17 || (slots >= 5 && waves8 > waves4))) shape = 1;
+            if (has8 && ((slots >= 17 && fills8) || (slots >= 5 && waves8 > waves4))) shape = 1;
             else if (has4 && (slots >= 5 || (L.cq > 2 * kSplitChunks4 && slots >= 3))) shape = 0;
-        } else if (L.cq > kSplitChunks8 && has8 && !is_pairs(L.layout) && slots >= 33) {
+        } else if (L.cq > kSplitChunks8 && has8 && !is_pairs(L.layout) && slots >= 33 && fills8) {
             shape = 1;
         }
     }
