@@ -184,6 +184,28 @@ def test_random_configurations(pb):
         run_layer(pb, W, bits, X, m, frac_bits=frac_bits, act_bits=act_bits, layout=lay)
 
 
+def test_random_configurations_of_the_multi_pass_kernels(pb):
+    """Seeded random widths and batches on both sides of every threshold at which the launcher takes the columns in
+    several passes (rows beyond 4096 columns with 33 and more operands on the bit layout, beyond 8192 columns from a
+    few operands on, four or eight operands per wave), with ragged last passes and groups that are not full."""
+    rng = np.random.default_rng(200300822 + 7)
+    for case in range(96):
+        R = int(rng.integers(1, 48))
+        if case % 2:
+            C = int(rng.integers(4097, 8193))
+            N = int(rng.choice([31, 32, 33, 36, 37, 40, 45, 64, 70]))
+        else:
+            C = int(rng.choice([rng.integers(8193, 12289), rng.integers(12289, 16385), rng.integers(16385, 32769)]))
+            N = int(rng.choice([2, 3, 4, 5, 8, 12, 16, 17, 21, 24, 25, 40]))
+        bits = int(rng.integers(1, 11))
+        m = sorted({int(rng.integers(1, bits + 1)), bits})
+        act_bits, frac_bits = [(32, 16), (32, 16), (16, 12), (8, 4)][int(rng.integers(0, 4))]
+        W, X = synth.ragged(R, C, batch=N, case=400 + case, xdist=["normal", "wide"][case % 3 == 0])
+        lay = GATES if (R % 4 == 0 and case % 5 == 0) else LAYOUTS["pair" if case % 4 >= 2 else "mfma"]
+        print("case", case, (R, C, N), "bits", bits, "m", m, "act", act_bits, frac_bits, hex(lay), flush=True)
+        run_layer(pb, W, bits, X, m, frac_bits=frac_bits, act_bits=act_bits, layout=lay)
+
+
 def test_fixed_point_conversion(pb):
     u = 2.0 ** -16
     special = [0.0, 1.0, -2.0, 0.5 * u, -0.5 * u, 1.5 * u, -1.5 * u, 1.0 - 2.0 ** -24, 32767.998046875, 32768.0,
