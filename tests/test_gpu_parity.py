@@ -402,6 +402,25 @@ def test_prepared_halves_equal_whole_call(pb, layout, fmt):
     assert (Y2.cpu().numpy().view(np.int32) == Y1.view(np.int32)).all()
 
 
+@pytest.mark.parametrize("lay", TILED)
+@pytest.mark.parametrize("shape_batch", [(60, 9000, 9), (33, 20000, 6), (40, 6000, 40)])
+def test_prepared_planes_on_the_multi_pass_kernels(pb, lay, shape_batch):
+    """Bit planes handed over in memory (pb_act_prep + pb_matmul_prepared) on rows and batches that the matrix-core
+    kernel takes in several passes over the columns: same bits as the call that converts the activations itself."""
+    R, C, N = shape_batch
+    W, X = synth.ragged(R, C, batch=N, case=31, xdist="wide")
+    bits, m = 6, 5
+    lin = pb.PackedLinear(dev(W), bits, max_batch=N, layout=LAYOUTS[lay])
+    ref = oracle_reference(W, bits, X, m)
+    Xd = dev(X)
+    Y1 = lin(Xd, m).cpu().numpy()
+    Y2 = torch.empty((N, R), dtype=torch.float32, device="cuda")
+    pb.pb_act_prep(lin.desc, Xd, N, lin.workspace)
+    pb.pb_matmul_prepared(lin.packed, lin.scales, lin.desc, m, N, Y2, lin.workspace)
+    assert_y_close(Y1, ref["Y"], ref["A"], ref["scales"])
+    assert (Y2.cpu().numpy().view(np.int32) == Y1.view(np.int32)).all()
+
+
 @pytest.mark.parametrize("fk", [(6, 8), (10, 16), (14, 16)])
 def test_narrow_activations_with_batch_and_saturation(pb, fk):
     """act_bits <= 16 (Section 3.1: fewer activation bits) on the matrix-core kernel; wide inputs saturate at k bits."""
